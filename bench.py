@@ -1,0 +1,305 @@
+#!/usr/bin/env python3
+"""Benchmark of the binarized conv / GEMM path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input.  The
+default workload is the binarized VGG-small stack at batch 256 (the one configuration
+that exercises every step: sign-encode, packed im2col, XOR-popcount GEMM, NCHW store,
+fp32 epilogue and the glue kernels).  Inputs and pre-encoded weights are resident in
+HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4|cfg2|cfg3|cfg5a|cfg5b]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+# Published MI355X figures used as roofline denominators.
+HBM_PEAK_GBS = 8000.0
+# Integer VALU: 256 CUs x 4 SIMDs x 16 lanes = 16384 32-bit lane-operations per clock at
+# 2.4 GHz (integer xor / popcount have no packed dual-issue form; this is half of the
+# chip's 157.3 TFLOP/s fp32 vector figure, which counts 2 flops per fma and packed fp32).
+VALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12  # 39.32
+BOPS_PER_LANEOP = 32.0  # 2 lane-instructions (xor, popcount-accumulate) per 32 bit-MACs = 64 binary ops
+
+# HBM bytes per GEMM launch from rocprofv3 counters (profiles/); None until measured.
+GEMM_TRAFFIC_BYTES = None
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg4", choices=["cfg4", "cfg2", "cfg3", "cfg5a", "cfg5b"])
+    ap.add_argument("--reading", default="A", choices=["A", "B"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the per-kernel side measurements")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def gemm_laneops(M, N, K):
+    return 2.0 * M * N * ((K + 31) // 32)
+
+
+def time_steps(fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return e0.elapsed_time(e1) / 1e3, wall
+
+
+def kernel_times(fn, reps):
+    """Per-kernel seconds per step from the library's HIP-event hook (same stream)."""
+    import torch
+    from paper_1911_04477_amd import binding as B
+    B.prof_enable(True)
+    try:
+        fn()
+        torch.cuda.synchronize()
+        tot = {}
+        cnt = {}
+        for _ in range(reps):
+            B.prof_reset()
+            fn()
+            torch.cuda.synchronize()
+            for name, ms in B.prof_records():
+                tot[name] = tot.get(name, 0.0) + ms / 1e3
+                cnt[name] = cnt.get(name, 0) + 1
+        return {k: v / reps for k, v in tot.items()}, {k: v // reps for k, v in cnt.items()}
+    finally:
+        B.prof_enable(False)
+
+
+def build_workload(name, args):
+    """Returns dict(fn, bops, gemm_shapes, label, oracle_fn(sample) -> (bops_done, seconds))."""
+    import torch
+    from paper_1911_04477_amd import binding as B
+    from paper_1911_04477_amd import inputs
+    dev = "cuda:0"
+
+    def up(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    if name == "cfg4":
+        from paper_1911_04477_amd.stack import VggStack
+        batch = 256
+        d = inputs.cfg4(batch=batch, reading=args.reading)
+        net = VggStack(d["layers"], d["params"], batch=batch, device=dev)
+        x = up(d["x"])
+        shapes = []
+        for L in d["layers"]:
+            if L.kind == "bconv":
+                shapes.append((L.cout, batch * L.hw * L.hw, L.cin * 9))
+            elif L.kind == "bfc":
+                shapes.append((batch, L.cout, L.cin))
+        bit_macs = inputs.stack_bit_macs(d["layers"], batch)
+
+        def oracle_sample(seconds):
+            import oracle
+            t0 = time.perf_counter()
+            oracle.vgg_stack(d["x"][:1], d["layers"], d["params"])
+            t1 = time.perf_counter() - t0
+            n = int(max(1, min(batch, seconds / max(t1, 1e-3))))
+            t0 = time.perf_counter()
+            oracle.vgg_stack(d["x"][:n], d["layers"], d["params"])
+            dt = time.perf_counter() - t0
+            return 2.0 * inputs.stack_bit_macs(d["layers"], n), dt, f"{n} of {batch} images through the whole stack"
+
+        return dict(fn=lambda: net.forward(x), bops=2.0 * bit_macs, gemm_shapes=shapes,
+                    label=f"cfg4_vgg_small_stack_b{batch}_reading{args.reading}", oracle=oracle_sample,
+                    extra={"batch": batch, "reading": args.reading})
+
+    if name == "cfg2":
+        d = inputs.cfg2()
+        s = inputs.CFG2
+        act, wp = up(d["act"]), B.bnn_encode(up(d["wt"]))
+        sc, bi = up(d["scale"]), up(d["bias"])
+        ap = torch.empty((s.M, B.packed_words(s.K)), dtype=torch.int64, device=dev)
+
+        def fn():
+            B.bnn_encode(act, ap)
+            B.bnn_xnor_gemm_epilogue(ap, wp, s.K, sc, bi, B.CH_COL)
+
+        def oracle_sample(seconds):
+            import oracle
+            rows = 16
+            t0 = time.perf_counter()
+            oracle.scale_bias(oracle.gemm_pm1(d["act"][:rows], d["wt"]), d["scale"], d["bias"], "col")
+            t1 = time.perf_counter() - t0
+            n = int(max(rows, min(s.M, rows * seconds / max(t1, 1e-3))))
+            t0 = time.perf_counter()
+            oracle.scale_bias(oracle.gemm_pm1(d["act"][:n], d["wt"]), d["scale"], d["bias"], "col")
+            return 2.0 * n * s.N * s.K, time.perf_counter() - t0, f"{n} of {s.M} activation rows"
+
+        return dict(fn=fn, bops=2.0 * s.M * s.N * s.K, gemm_shapes=[(s.M, s.N, s.K)], label="cfg2_binarized_fc_256x4096x4096",
+                    oracle=oracle_sample, extra={})
+
+    shape = {"cfg3": inputs.CFG3, "cfg5a": inputs.CFG5A, "cfg5b": inputs.CFG5B}[name]
+    d = {"cfg3": inputs.cfg3, "cfg5a": inputs.cfg5a, "cfg5b": inputs.cfg5b}[name]()
+    x, wp = up(d["x"]), B.bnn_pack_conv_weight(up(d["w"]))
+    st, pd = (shape.sH, shape.sW), (shape.pH, shape.pW)
+    ws = torch.empty(B.conv2d_workspace_bytes(x.shape, shape.kH, shape.kW, st, pd), dtype=torch.uint8, device=dev)
+    out = torch.empty((shape.N, shape.D, shape.OH, shape.OW), dtype=torch.int32, device=dev)
+
+    def fn():
+        B.bnn_conv2d(x, wp, shape.D, shape.kH, shape.kW, st, pd, want_int=True, workspace=ws, out_i32=out)
+
+    def oracle_sample(seconds):
+        import oracle
+        t0 = time.perf_counter()
+        oracle.conv2d_pm1(d["x"][:1], d["w"], st, pd)
+        t1 = time.perf_counter() - t0
+        n = int(max(1, min(shape.N, seconds / max(t1, 1e-3))))
+        t0 = time.perf_counter()
+        oracle.conv2d_pm1(d["x"][:n], d["w"], st, pd)
+        return 2.0 * shape.bit_macs * n / shape.N, time.perf_counter() - t0, f"{n} of {shape.N} images"
+
+    return dict(fn=fn, bops=2.0 * shape.bit_macs, gemm_shapes=[(shape.D, shape.P, shape.K)],
+                label=f"{name}_binarized_conv_{shape.N}x{shape.C}x{shape.H}x{shape.W}_to_{shape.D}_k{shape.kH}s{shape.sH}p{shape.pH}",
+                oracle=oracle_sample, extra={})
+
+
+def side_measurements():
+    """Streaming kernels against the HBM roof, the VALU probe, and the other configurations."""
+    import torch
+    from paper_1911_04477_amd import binding as B
+    from paper_1911_04477_amd import inputs
+    dev = "cuda:0"
+    res = {}
+
+    def t(fn, reps=20, warm=3):
+        s, _ = time_steps(fn, reps, warm)
+        return s / reps
+
+    # plain copy: the achievable-HBM yardstick (1 GiB read + 1 GiB written)
+    n = 1 << 30
+    a = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
+    b = torch.empty(n, dtype=torch.uint8, device=dev)
+    dt = t(lambda: B.bnn_copy_probe(a, b))
+    res["copy_probe_GBs"] = round(2 * n / dt / 1e9, 1)
+    del b
+    # row-major encode, 1 GiB of fp32 (streams from HBM) and the cfg2 weight matrix (64 MiB)
+    src = a.view(torch.float32).view(-1, 4096)
+    dst = torch.empty((src.shape[0], 64), dtype=torch.int64, device=dev)
+    dt = t(lambda: B.bnn_encode(src, dst))
+    res["encode_1GiB_GBs"] = round((src.numel() * 4 + dst.numel() * 8) / dt / 1e9, 1)
+    w = src[:4096]
+    dt = t(lambda: B.bnn_encode(w, dst[:4096]))
+    res["encode_cfg2_weights_GBs"] = round((w.numel() * 4 + 4096 * 64 * 8) / dt / 1e9, 1)
+    del src, dst, a
+    # input encode + packed im2col at the conv configurations
+    for name, shape in (("cfg3", inputs.CFG3), ("cfg5a", inputs.CFG5A), ("cfg5b", inputs.CFG5B)):
+        x = torch.randn((shape.N, shape.C, shape.H, shape.W), device=dev)
+        geo = (shape.kH, shape.kW, (shape.sH, shape.sW), (shape.pH, shape.pW))
+        fn = lambda: B.bnn_im2col_packed(x, *geo)
+        kt, _ = kernel_times(fn, 5)
+        Cw = B.packed_words(shape.C)
+        Kw = B.conv_kwords(shape.C, shape.kH, shape.kW)
+        if "encode_nchw" in kt:
+            if shape.kH == 1:
+                byts = shape.P * shape.C * 4 + shape.P * Cw * 8
+            else:
+                byts = x.numel() * 4 + shape.N * shape.H * shape.W * Cw * 8
+            res[f"{name}_encode_nchw_GBs"] = round(byts / kt["encode_nchw"] / 1e9, 1)
+        if "im2col_gather" in kt:
+            byts = shape.P * Kw * 8 + shape.N * shape.H * shape.W * Cw * 8
+            res[f"{name}_im2col_gather_GBs"] = round(byts / kt["im2col_gather"] / 1e9, 1)
+        tot = sum(kt.values())
+        res[f"{name}_im2col_total_GBs"] = round((x.numel() * 4 * (0.25 if shape.sH == 2 else 1.0) + shape.P * Kw * 8) / tot / 1e9, 1)
+        del x
+    # VALU probe: measured ceiling of xor + popcount-accumulate lane-ops
+    blocks, iters = 256 * 16, 2000
+    sink = torch.empty(blocks * 256, dtype=torch.int32, device=dev)
+    dt = t(lambda: B.bnn_valu_peak_probe(sink, blocks, iters), reps=5, warm=2)
+    res["valu_probe_Tlaneops"] = round(blocks * 256 * iters * 128 / dt / 1e12, 2)
+    return res
+
+
+def other_configs(args):
+    out = {}
+    for name in ("cfg2", "cfg3", "cfg5a", "cfg5b"):
+        wl = build_workload(name, args)
+        s, _ = time_steps(wl["fn"], 20, 3)
+        per = s / 20
+        kt, _ = kernel_times(wl["fn"], 5)
+        g = sum(v for k, v in kt.items() if k.startswith("xnor_gemm"))
+        lane = sum(gemm_laneops(*sh) for sh in wl["gemm_shapes"])
+        out[name] = {"TBOPS_end_to_end": round(wl["bops"] / per / 1e12, 2), "ms": round(per * 1e3, 4),
+                     "TBOPS_gemm_only": round(wl["bops"] / g / 1e12, 2),
+                     "gemm_frac_valu_peak": round(lane / g / 1e12 / VALU_PEAK_TLANEOPS, 4),
+                     "kernels_ms": {k: round(v * 1e3, 4) for k, v in kt.items()}}
+        del wl
+    return out
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_1911_04477_amd import binding as B
+    B.lib()  # fail loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    wl = build_workload(args.workload, args)
+    secs, _wall = time_steps(wl["fn"], args.steps, args.warmup)
+    per_step = secs / args.steps
+    value = wl["bops"] / per_step / 1e12
+
+    # dominant kernel: the XOR-popcount GEMM, timed with HIP events on the launch stream
+    kt, kc = kernel_times(wl["fn"], max(3, min(args.steps, 10)))
+    gemm_s = sum(v for k, v in kt.items() if k.startswith("xnor_gemm"))
+    gemm_launches = sum(v for k, v in kc.items() if k.startswith("xnor_gemm"))
+    lane_ops = sum(gemm_laneops(*sh) for sh in wl["gemm_shapes"])
+    achieved = lane_ops / gemm_s / 1e12
+    roofline = {
+        "kernel": "xnor_gemm", "bound": "alu", "achieved": round(achieved, 3), "peak": round(VALU_PEAK_TLANEOPS, 2),
+        "unit": "Tlaneop/s", "frac": round(achieved / VALU_PEAK_TLANEOPS, 4), "traffic": GEMM_TRAFFIC_BYTES,
+        "launches_per_step": gemm_launches, "avg_launch_ms": round(gemm_s / max(gemm_launches, 1) * 1e3, 4),
+        "gemm_only_TBOPS": round(wl["bops"] / gemm_s / 1e12, 2),
+        "note": "achieved = 2*M*N*ceil(K/32) lane-ops summed over the step's GEMM launches / their summed HIP-event time",
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        done, dt, what = wl["oracle"](args.cpu_seconds)
+        cpu = {"value": round(done / dt / 1e12, 6), "unit": "TBOPS", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": what, "seconds": round(dt, 2)}
+
+    line = {
+        "metric": "binary_ops_per_sec", "value": round(value, 3), "unit": "TBOPS", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(per_step * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32", "data": "synthetic",
+        "config": dict({"workload": wl["label"]}, **wl["extra"]),
+        "roofline": roofline, "cpu_baseline": cpu,
+        "kernels_ms_per_step": {k: round(v * 1e3, 4) for k, v in kt.items()},
+    }
+    if not args.no_extras:
+        line["streaming"] = side_measurements()
+        line["hbm_peak_GBs"] = HBM_PEAK_GBS
+        line["other_configs"] = other_configs(args)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,219 @@
+/*
+ * bnn.h -- C ABI of the MI355X (gfx950) binarized convolution / GEMM library.
+ *
+ * The library implements the forward path of a binarized convolutional layer as
+ * described in "A Computing Kernel for Network Binarization on PyTorch"
+ * (arXiv 1911.04477): tensors are sign-encoded into 1-bit words (section 3.1),
+ * the input is im2col-lowered (section 2.1) and the Gemm-Accumulation is replaced
+ * by Xnor-Bitcount (section 3.2).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Pointers named in the argument lists are DEVICE pointers unless stated
+ *    otherwise.  The caller owns every buffer; the library allocates and frees no
+ *    device memory and never synchronises: work is enqueued on `stream`
+ *    (a hipStream_t passed as void*; NULL = the default stream).
+ *  - Base pointers must be 16-byte aligned (BNN_ERR_ALIGN otherwise).
+ *  - All argument checks happen on the host before any launch; on error nothing
+ *    is launched.  A failed launch is reported as BNN_ERR_HIP.
+ *  - Empty problems (a zero row / column / batch count) return BNN_OK without a
+ *    launch.  A reduction length K <= 0 is BNN_ERR_SHAPE.
+ *
+ * Packed format (part of the ABI; section 3.1: value -1 <-> bit 0, +1 <-> bit 1)
+ * -----------------------------------------------------------------------------
+ *  A packed row of K binary values is ceil(K/64) uint64 words.  Element k lives in
+ *  bit (k mod 64), least-significant bit first, of word (k div 64).  Bits past K in
+ *  the last word are 0.  On a little-endian machine the same bytes viewed as
+ *  uint32 are the paper's uint32_t packing with 32 values per word.
+ *  Binarization is Sign(x) (section 4.2) with the predicate x >= 0:  +0.0 and -0.0
+ *  encode as 1, negative values and NaN as 0.
+ *
+ * Packed convolution operands
+ * ---------------------------
+ *  The reduction axis of a convolution is ordered (kh, kw, c) with c innermost, and
+ *  every tap (kh, kw) owns ceil(C/64) whole words (pad bits 0 in BOTH operands), so
+ *  a packed patch / filter row has bnn_conv_kwords(C,kH,kW) = kH*kW*ceil(C/64)
+ *  words.  Because the exclusive-or of two pad bits is 0 they do not contribute,
+ *  and the result uses the true K = C*kH*kW.
+ */
+#ifndef BNN_H_
+#define BNN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  BNN_OK = 0,
+  BNN_ERR_NULL = 1,        /* a required pointer is NULL */
+  BNN_ERR_SHAPE = 2,       /* a dimension is negative, K <= 0, or an output dimension is < 1 */
+  BNN_ERR_STRIDE = 3,      /* a leading dimension is smaller than the row it must hold */
+  BNN_ERR_ALIGN = 4,       /* a base pointer is not 16-byte aligned */
+  BNN_ERR_WORKSPACE = 5,   /* workspace_bytes is smaller than the matching *_workspace_bytes() */
+  BNN_ERR_HIP = 6,         /* the HIP runtime reported an error at launch */
+  BNN_ERR_UNSUPPORTED = 7  /* valid request outside the implemented range (sizes over 2^31 elements per operand, ...) */
+} bnn_status;
+
+typedef enum { BNN_CH_NONE = 0, BNN_CH_ROW = 1, BNN_CH_COL = 2 } bnn_ch_axis;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char *bnn_status_str(bnn_status s);
+
+/* ceil(K/64): uint64 words per packed row of K values; 0 for K <= 0. */
+int64_t bnn_packed_words(int64_t K);
+
+/* kH*kW*ceil(C/64): words per packed patch / filter row; 0 for non-positive input. */
+int64_t bnn_conv_kwords(int C, int kH, int kW);
+
+/* floor((in + 2*pad - k)/stride) + 1, or 0 when that is not positive / arguments invalid. */
+int64_t bnn_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad);
+
+/*
+ * bnn_encode -- sign-encode a row-major fp32 matrix along its rows (section 3.1,
+ * "encoded in the direction of rows"; the paper packs 32 values per uint32_t).
+ *   src     [rows, K] fp32, row stride src_ld floats (src_ld >= K)
+ *   dst     [rows, ceil(K/64)] uint64, row stride dst_ld words (dst_ld >= ceil(K/64));
+ *           pad bits of the last word are written as 0; words between ceil(K/64)
+ *           and dst_ld are not touched.
+ */
+bnn_status bnn_encode(const float *src, int64_t rows, int64_t K, int64_t src_ld, uint64_t *dst,
+                      int64_t dst_ld, void *stream);
+
+/*
+ * bnn_pack_conv_weight -- encode a filter bank (section 3.1: the weight skips im2col
+ * and is stored pre-encoded as a [D, K^2 C / wordsize] bit matrix).
+ *   w         [D, C, kH, kW] fp32 contiguous
+ *   w_packed  [D, bnn_conv_kwords(C,kH,kW)] uint64 contiguous, (kh, kw, c) order.
+ */
+bnn_status bnn_pack_conv_weight(const float *w, int D, int C, int kH, int kW, uint64_t *w_packed,
+                                void *stream);
+
+/*
+ * bnn_im2col_packed -- lower an fp32 NCHW image batch to packed patch rows
+ * (section 2.1 im2col, section 3.1 input encoding).  The fp32 input is zero-padded
+ * BEFORE binarization, so a tap outside the image encodes as +1 (bit 1) for each of
+ * the C real channels.
+ *   x     [N, C, H, W] fp32 contiguous
+ *   cols  [N*OH*OW, bnn_conv_kwords(C,kH,kW)] uint64 contiguous; row p = (n*OH + oh)*OW + ow
+ *   workspace  scratch of at least bnn_im2col_workspace_bytes(...) bytes (may be NULL
+ *              when that is 0); contents undefined afterwards.
+ */
+bnn_status bnn_im2col_packed(const float *x, int N, int C, int H, int W, int kH, int kW, int sH,
+                             int sW, int pH, int pW, uint64_t *cols, void *workspace,
+                             size_t workspace_bytes, void *stream);
+size_t bnn_im2col_workspace_bytes(int N, int C, int H, int W, int kH, int kW, int sH, int sW,
+                                  int pH, int pW);
+
+/*
+ * bnn_xnor_gemm -- Xnor-Bitcount GEMM (section 3.2, Table 1) in the exclusive-or
+ * form, valid for every K:   C[m,n] = K - 2 * sum_w popcount(A[m,w] XOR B[n,w]).
+ * For K a multiple of 32 this equals the paper's sum of 2*Bitcount(xnor) - 32.
+ *   A  [M, ceil(K/64)] uint64, row stride lda words;  B  [N, ceil(K/64)], row stride ldb
+ *      (both operands K-contiguous).  Bits past K in the last word are ignored
+ *      (masked), whatever they hold.
+ *   C  [M, N] int32 row-major, row stride ldc elements (ldc >= N).
+ */
+bnn_status bnn_xnor_gemm(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb, int32_t *C,
+                         int64_t ldc, int64_t M, int64_t N, int64_t K, void *stream);
+
+/*
+ * bnn_xnor_gemm_epilogue -- the same GEMM followed by the per-channel affine map that
+ * stands for the bias step of the forward graph (section 2.2):
+ *   Y[m,n] = fma(scale[ch], (float)C[m,n], bias[ch])   (one rounding),
+ *   ch = m for BNN_CH_ROW, n for BNN_CH_COL.
+ *   C (int32, ldc) and Y (fp32, ldy) may each be NULL, not both.  With Y non-NULL,
+ *   scale and bias are required (M or N floats according to axis) and axis must not
+ *   be BNN_CH_NONE.
+ */
+bnn_status bnn_xnor_gemm_epilogue(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb,
+                                  int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc, float *Y,
+                                  int64_t ldy, const float *scale, const float *bias,
+                                  bnn_ch_axis axis, void *stream);
+
+/*
+ * bnn_conv2d -- binarized convolution forward (the forward graph of Figure 3):
+ * input encode + packed im2col, Xnor-Bitcount GEMM against the pre-encoded filter
+ * bank, result written straight into the NCHW output (no col2im pass), optional
+ * per-output-channel affine map.
+ *   x         [N, C, H, W] fp32 contiguous
+ *   w_packed  [D, bnn_conv_kwords(C,kH,kW)] uint64 from bnn_pack_conv_weight
+ *   out_i32   [N, D, OH, OW] int32 or NULL;  out_f32 same shape fp32 or NULL (not both NULL)
+ *   scale, bias  [D] fp32, required iff out_f32 != NULL:
+ *             out_f32 = fma(scale[d], (float)acc, bias[d])
+ *   workspace at least bnn_conv2d_workspace_bytes(...) bytes.
+ */
+bnn_status bnn_conv2d(const float *x, const uint64_t *w_packed, int N, int C, int H, int W, int D,
+                      int kH, int kW, int sH, int sW, int pH, int pW, int32_t *out_i32,
+                      float *out_f32, const float *scale, const float *bias, void *workspace,
+                      size_t workspace_bytes, void *stream);
+size_t bnn_conv2d_workspace_bytes(int N, int C, int H, int W, int kH, int kW, int sH, int sW, int pH,
+                                  int pW);
+
+/* ---- glue kernels of the binarized VGG-small stack (not part of the paper's kernel,
+ *      which covers convolution only -- section 4.4) -------------------------------- */
+
+/*
+ * bnn_maxpool2x2 -- 2x2 / stride-2 max-pool on int32 planes, optionally followed by the
+ * affine map on the pooled value.
+ *   in       [N, D, H, W] int32 (H, W even);  out_i32 / out_f32 [N, D, H/2, W/2], one may be NULL
+ *   out_f32 = fma(scale[d], (float)max, bias[d]);  scale, bias [D] required iff out_f32.
+ */
+bnn_status bnn_maxpool2x2(const int32_t *in, int N, int D, int H, int W, int32_t *out_i32,
+                          float *out_f32, const float *scale, const float *bias, void *stream);
+
+/*
+ * bnn_conv2d_f32 -- real-valued convolution for the first layer of the stack.
+ * Summation order is fixed: acc = 0; for c, kh, kw (row-major): acc = fma(x, w, acc)
+ * with zero padding; then, when scale != NULL, out = fma(scale[d], acc, bias[d]).
+ *   x [N,C,H,W], w [D,C,kH,kW], out [N,D,OH,OW], all fp32 contiguous.
+ */
+bnn_status bnn_conv2d_f32(const float *x, const float *w, int N, int C, int H, int W, int D, int kH,
+                          int kW, int sH, int sW, int pH, int pW, const float *scale,
+                          const float *bias, float *out, void *stream);
+
+/*
+ * bnn_fc_f32 -- real-valued fully-connected layer for the last layer of the stack.
+ *   out[m,n] = (acc = 0; for k ascending: acc = fma(xk, w[n,k], acc)) + bias[n]
+ *   where xk = x[m,k], or its binary value (x >= 0 ? +1 : -1) when sign_input != 0.
+ *   x [M,K], w [N,K], bias [N] or NULL, out [M,N], all fp32 contiguous.
+ */
+bnn_status bnn_fc_f32(const float *x, const float *w, const float *bias, int64_t M, int64_t K,
+                      int64_t N, int sign_input, float *out, void *stream);
+
+/* ---- measurement helpers ------------------------------------------------------------ */
+
+/*
+ * Kernel timing.  While enabled, every kernel the library launches is bracketed by a
+ * pair of HIP events recorded on the caller's stream (host objects, created on first
+ * use and kept until bnn_prof_enable(0)).  At most BNN_PROF_MAX_RECORDS launches are
+ * recorded between two resets; later ones run untimed.  Not thread-safe.
+ */
+#define BNN_PROF_MAX_RECORDS 4096
+bnn_status bnn_prof_enable(int enable);
+bnn_status bnn_prof_reset(void);
+int64_t bnn_prof_count(void);
+/* Synchronises on record i's end event, then returns its kernel id and duration. */
+bnn_status bnn_prof_get(int64_t i, int *kernel_id, float *milliseconds);
+const char *bnn_kernel_name(int kernel_id);
+
+/*
+ * bnn_valu_peak_probe -- a microbenchmark, not part of the method: every lane runs
+ * `iters` rounds of 64 independent xor + popcount-accumulate pairs from registers
+ * (2 * 64 * iters VALU lane-operations per lane) and the grid is `blocks` workgroups
+ * of 256 threads.  sink [blocks*256] int32 receives a value that depends on all of them.
+ */
+bnn_status bnn_valu_peak_probe(int32_t *sink, int blocks, int iters, void *stream);
+
+/*
+ * bnn_copy_probe -- plain device copy of n_bytes (multiple of 16) used as the yardstick
+ * for achievable HBM bandwidth and for scaling hardware byte counters.
+ */
+bnn_status bnn_copy_probe(const void *src, void *dst, size_t n_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BNN_H_ */

@@ -1,0 +1,100 @@
+// Internal helpers shared by the translation units of libbnn (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "bnn.h"
+
+namespace bnn {
+
+// Kernel ids reported by the timing hook.
+enum KernelId : int {
+  KID_ENCODE_ROWS = 0,
+  KID_PACK_CONV_WEIGHT = 1,
+  KID_ENCODE_NCHW = 2,
+  KID_IM2COL_GATHER = 3,
+  KID_XNOR_GEMM = 4,
+  KID_MAXPOOL = 5,
+  KID_CONV_F32 = 6,
+  KID_FC_F32 = 7,
+  KID_VALU_PROBE = 8,
+  KID_COPY_PROBE = 9,
+  KID_XNOR_GEMM_SMALL = 10,
+  KID_COUNT = 11
+};
+
+// Timing hook: records an event pair around a launch when profiling is on.
+void prof_begin(int kernel_id, hipStream_t s);
+void prof_end(hipStream_t s);
+
+struct ProfScope {
+  hipStream_t s;
+  ProfScope(int kid, hipStream_t st) : s(st) { prof_begin(kid, st); }
+  ~ProfScope() { prof_end(s); }
+};
+
+inline bnn_status launch_status() {
+  return hipGetLastError() == hipSuccess ? BNN_OK : BNN_ERR_HIP;
+}
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Division of a 32-bit unsigned value by a runtime constant with one mulhi and one
+// shift (round-up method; exact for every n < 2^31 and 1 <= d < 2^31).
+struct FastDiv {
+  uint32_t d, mul, shift;
+  __host__ __device__ FastDiv() : d(1), mul(0), shift(0) {}
+  __host__ __device__ explicit FastDiv(uint32_t div) : d(div) {
+    if (div == 1) {
+      mul = 0;
+      shift = 0;
+      return;
+    }
+    uint32_t l = 0;
+    while ((1ull << l) < div) ++l;  // l = ceil(log2 d)
+    shift = l - 1;
+    // m = floor(2^32 * (2^l - d) / d) + 1, used as q = (mulhi(n, m) + n) >> l, rewritten
+    // below so that no 33-bit intermediate is needed for n < 2^31.
+    mul = (uint32_t)(((1ull << 32) * ((1ull << l) - div)) / div + 1);
+  }
+};
+
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) {
+  if (f.d == 1) return n;
+  uint32_t t = __umulhi(n, f.mul);
+  return (t + ((n - t) >> 1)) >> f.shift;
+}
+
+// ---- cross-file internals ---------------------------------------------------------------
+struct GemmParams {
+  const uint32_t *A;   // [M, lda32] dwords
+  const uint64_t *B;   // [N, ldb] words
+  int64_t lda32, ldb;
+  int M, N;
+  int Kd;              // dwords per row that hold bits of the reduction (ceil(Kbits/32))
+  int Kbits;           // bits per row taking part in the exclusive-or
+  int Kformula;        // K of the formula (true reduction length)
+  int Kw64;            // words per row that may be read (ceil(Kbits/64))
+  int b_vec16;         // B rows may be read with 16-byte loads
+  int32_t *C;
+  float *Y;
+  int64_t ldc, ldy;    // row (m) strides of C and Y
+  const float *scale, *bias;
+  int axis;
+  uint32_t OHW;        // columns per image; n -> (img, pix) = (n / OHW, n % OHW)
+  FastDiv divOHW;
+  int64_t img_stride;  // elements between images in C / Y
+  int tilesM, tilesN;
+};
+
+
+// Launch the exclusive-or / popcount GEMM described by p (tilesM / tilesN are filled in).
+bnn_status run_gemm(GemmParams &p, hipStream_t s);
+
+// Conv helpers (im2col.hip).  check_conv_geometry validates shapes and 32-bit limits;
+// run_im2col launches encode (+ gather) with already validated arguments.
+bnn_status check_conv_geometry(int N, int C, int H, int W, int kH, int kW, int sH, int sW, int pH, int pW);
+bnn_status run_im2col(const float *x, int N, int C, int H, int W, int kH, int kW, int sH, int sW, int pH, int pW,
+                      uint64_t *cols, void *workspace, hipStream_t s);
+
+}  // namespace bnn

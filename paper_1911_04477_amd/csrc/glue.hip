@@ -1,0 +1,196 @@
+// Glue kernels of the binarized VGG-small stack and the two measurement probes.
+// The paper's kernel covers the convolution only (section 4.4); these are the minimal
+// correctness-first pieces around it.  The fp32 layers use one thread per output and a
+// fixed sequential fma order so that their rounding is reproducible bit for bit (a
+// differently rounded value could flip a sign that the next binarized layer consumes).
+#include "common.h"
+
+namespace bnn {
+
+__global__ __launch_bounds__(256) void maxpool2x2_kernel(const int32_t *__restrict__ in, int D, int H, int W,
+                                                         int32_t *__restrict__ out_i32, float *__restrict__ out_f32,
+                                                         const float *__restrict__ scale,
+                                                         const float *__restrict__ bias, FastDiv divOW, FastDiv divOH,
+                                                         FastDiv divD, uint32_t total) {
+  const uint32_t o = blockIdx.x * 256u + threadIdx.x;
+  if (o >= total) return;
+  const uint32_t OW = W / 2, OH = H / 2;
+  const uint32_t t = fdiv(o, divOW);
+  const uint32_t ow = o - t * OW;
+  const uint32_t plane = fdiv(t, divOH);
+  const uint32_t oh = t - plane * OH;
+  const int2 r0 = *reinterpret_cast<const int2 *>(in + ((size_t)plane * H + 2 * oh) * W + 2 * ow);
+  const int2 r1 = *reinterpret_cast<const int2 *>(in + ((size_t)plane * H + 2 * oh + 1) * W + 2 * ow);
+  const int m = max(max(r0.x, r0.y), max(r1.x, r1.y));
+  if (out_i32) out_i32[o] = m;
+  if (out_f32) {
+    const uint32_t d = plane - fdiv(plane, divD) * D;
+    out_f32[o] = fmaf(scale[d], (float)m, bias[d]);
+  }
+}
+
+__global__ __launch_bounds__(256) void conv2d_f32_kernel(const float *__restrict__ x, const float *__restrict__ w,
+                                                         int C, int H, int W, int D, int kH, int kW, int sH, int sW,
+                                                         int pH, int pW, int OH, int OW,
+                                                         const float *__restrict__ scale,
+                                                         const float *__restrict__ bias, float *__restrict__ out,
+                                                         FastDiv divOW, FastDiv divOH, FastDiv divD, uint32_t total) {
+  const uint32_t o = blockIdx.x * 256u + threadIdx.x;
+  if (o >= total) return;
+  const uint32_t t = fdiv(o, divOW);
+  const uint32_t ow = o - t * OW;
+  const uint32_t t2 = fdiv(t, divOH);
+  const uint32_t oh = t - t2 * OH;
+  const uint32_t n = fdiv(t2, divD);
+  const uint32_t d = t2 - n * D;
+  float acc = 0.0f;
+  for (int c = 0; c < C; ++c)
+    for (int kh = 0; kh < kH; ++kh)
+      for (int kw = 0; kw < kW; ++kw) {
+        const int ih = (int)(oh * sH) + kh - pH, iw = (int)(ow * sW) + kw - pW;
+        float xv = 0.0f;
+        if (ih >= 0 && ih < H && iw >= 0 && iw < W) xv = x[(((size_t)n * C + c) * H + ih) * W + iw];
+        acc = fmaf(xv, w[(((size_t)d * C + c) * kH + kh) * kW + kw], acc);
+      }
+  if (scale) acc = fmaf(scale[d], acc, bias[d]);
+  out[o] = acc;
+}
+
+__global__ __launch_bounds__(256) void fc_f32_kernel(const float *__restrict__ x, const float *__restrict__ w,
+                                                     const float *__restrict__ bias, int64_t M, int64_t K, int64_t N,
+                                                     int sign_input, float *__restrict__ out) {
+  const int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (o >= M * N) return;
+  const int64_t m = o / N, n = o - m * N;
+  const float *xr = x + m * K, *wr = w + n * K;
+  float acc = 0.0f;
+  for (int64_t k = 0; k < K; ++k) {
+    float xv = xr[k];
+    if (sign_input) xv = xv >= 0.0f ? 1.0f : -1.0f;
+    acc = fmaf(xv, wr[k], acc);
+  }
+  if (bias) acc = acc + bias[n];
+  out[o] = acc;
+}
+
+// 64 independent xor + popcount-accumulate pairs per round; the xor operand changes every
+// round so nothing can be hoisted.
+__global__ __launch_bounds__(256) void valu_probe_kernel(int32_t *__restrict__ sink, int iters) {
+  const uint32_t tid = blockIdx.x * 256u + threadIdx.x;
+  uint32_t b[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) b[j] = tid * 2654435761u + j * 40503u;
+  int acc[64];
+#pragma unroll
+  for (int i = 0; i < 64; ++i) acc[i] = 0;
+  uint32_t a = 0x9e3779b9u ^ tid;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 64; ++i) acc[i] = __builtin_popcount((a + i) ^ b[i & 7]) + acc[i];
+    a = a * 1664525u + 1013904223u;
+  }
+  int tot = 0;
+#pragma unroll
+  for (int i = 0; i < 64; ++i) tot += acc[i];
+  sink[tid] = tot;
+}
+
+__global__ __launch_bounds__(256) void copy_probe_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
+                                                         size_t n16) {
+  size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
+#pragma unroll
+  for (int u = 0; u < 4; ++u, i += 256)
+    if (i < n16) dst[i] = src[i];
+}
+
+}  // namespace bnn
+
+using namespace bnn;
+
+extern "C" bnn_status bnn_maxpool2x2(const int32_t *in, int N, int D, int H, int W, int32_t *out_i32, float *out_f32,
+                                     const float *scale, const float *bias, void *stream) {
+  if (N < 0 || D < 0 || H <= 0 || W <= 0 || (H & 1) || (W & 1)) return BNN_ERR_SHAPE;
+  if (N == 0 || D == 0) return BNN_OK;
+  if (!in || (!out_i32 && !out_f32)) return BNN_ERR_NULL;
+  if (out_f32 && (!scale || !bias)) return BNN_ERR_NULL;
+  if (!aligned16(in) || (out_i32 && !aligned16(out_i32)) || (out_f32 && !aligned16(out_f32))) return BNN_ERR_ALIGN;
+  const int64_t total = (int64_t)N * D * (H / 2) * (W / 2);
+  if (total > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  {
+    ProfScope ps(KID_MAXPOOL, s);
+    hipLaunchKernelGGL(maxpool2x2_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, in, D, H, W, out_i32,
+                       out_f32, scale, bias, FastDiv((uint32_t)(W / 2)), FastDiv((uint32_t)(H / 2)),
+                       FastDiv((uint32_t)D), (uint32_t)total);
+  }
+  return launch_status();
+}
+
+extern "C" bnn_status bnn_conv2d_f32(const float *x, const float *w, int N, int C, int H, int W, int D, int kH, int kW,
+                                     int sH, int sW, int pH, int pW, const float *scale, const float *bias, float *out,
+                                     void *stream) {
+  bnn_status st = check_conv_geometry(N, C, H, W, kH, kW, sH, sW, pH, pW);
+  if (st != BNN_OK) return st;
+  if (D < 0) return BNN_ERR_SHAPE;
+  if (N == 0 || D == 0) return BNN_OK;
+  if (!x || !w || !out) return BNN_ERR_NULL;
+  if ((scale == nullptr) != (bias == nullptr)) return BNN_ERR_NULL;
+  if (!aligned16(x) || !aligned16(w) || !aligned16(out)) return BNN_ERR_ALIGN;
+  const int64_t OH = bnn_conv_out_dim(H, kH, sH, pH), OW = bnn_conv_out_dim(W, kW, sW, pW);
+  const int64_t total = (int64_t)N * D * OH * OW;
+  if (total > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  {
+    ProfScope ps(KID_CONV_F32, s);
+    hipLaunchKernelGGL(conv2d_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, x, w, C, H, W, D, kH,
+                       kW, sH, sW, pH, pW, (int)OH, (int)OW, scale, bias, out, FastDiv((uint32_t)OW),
+                       FastDiv((uint32_t)OH), FastDiv((uint32_t)D), (uint32_t)total);
+  }
+  return launch_status();
+}
+
+extern "C" bnn_status bnn_fc_f32(const float *x, const float *w, const float *bias, int64_t M, int64_t K, int64_t N,
+                                 int sign_input, float *out, void *stream) {
+  if (M < 0 || N < 0 || K <= 0) return BNN_ERR_SHAPE;
+  if (M == 0 || N == 0) return BNN_OK;
+  if (!x || !w || !out) return BNN_ERR_NULL;
+  if (!aligned16(x) || !aligned16(w) || !aligned16(out)) return BNN_ERR_ALIGN;
+  if (M * N > 0x7fffffffLL * 128) return BNN_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  {
+    ProfScope ps(KID_FC_F32, s);
+    hipLaunchKernelGGL(fc_f32_kernel, dim3((unsigned)((M * N + 255) / 256)), dim3(256), 0, s, x, w, bias, M, K, N,
+                       sign_input, out);
+  }
+  return launch_status();
+}
+
+extern "C" bnn_status bnn_valu_peak_probe(int32_t *sink, int blocks, int iters, void *stream) {
+  if (blocks < 0 || iters < 0) return BNN_ERR_SHAPE;
+  if (blocks == 0) return BNN_OK;
+  if (!sink) return BNN_ERR_NULL;
+  if (!aligned16(sink)) return BNN_ERR_ALIGN;
+  hipStream_t s = (hipStream_t)stream;
+  {
+    ProfScope ps(KID_VALU_PROBE, s);
+    hipLaunchKernelGGL(valu_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, s, sink, iters);
+  }
+  return launch_status();
+}
+
+extern "C" bnn_status bnn_copy_probe(const void *src, void *dst, size_t n_bytes, void *stream) {
+  if (n_bytes % 16) return BNN_ERR_SHAPE;
+  if (n_bytes == 0) return BNN_OK;
+  if (!src || !dst) return BNN_ERR_NULL;
+  if (!aligned16(src) || !aligned16(dst)) return BNN_ERR_ALIGN;
+  const size_t n16 = n_bytes / 16;
+  const size_t blocks = (n16 + 1023) / 1024;
+  if (blocks > 0x7fffffffULL) return BNN_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  {
+    ProfScope ps(KID_COPY_PROBE, s);
+    hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4 *)src, (uint4 *)dst,
+                       n16);
+  }
+  return launch_status();
+}

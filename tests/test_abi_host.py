@@ -1,0 +1,166 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header
+declares, the size helpers agree with their definitions and every argument error is
+reported before anything is launched (so these run without a GPU)."""
+import os
+import re
+
+import pytest
+
+from paper_1911_04477_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, NULL, SHAPE, STRIDE, ALIGN, WORKSPACE, HIP, UNSUPPORTED = range(8)
+
+
+@pytest.fixture(scope="module")
+def L():
+    return B.lib()
+
+
+def _declared_functions():
+    src = open(os.path.join(ROOT, "include", "bnn.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(bnn_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported_and_bound(L):
+    names = _declared_functions()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(names) == set(B.SIGNATURES), set(names) ^ set(B.SIGNATURES)
+
+
+def test_status_strings(L):
+    expect = ["BNN_OK", "BNN_ERR_NULL", "BNN_ERR_SHAPE", "BNN_ERR_STRIDE", "BNN_ERR_ALIGN", "BNN_ERR_WORKSPACE",
+              "BNN_ERR_HIP", "BNN_ERR_UNSUPPORTED"]
+    for i, s in enumerate(expect):
+        assert L.bnn_status_str(i).decode() == s
+    assert L.bnn_status_str(99).decode() == "BNN_ERR_UNKNOWN"
+
+
+def test_size_helpers(L):
+    for K, w in [(-1, 0), (0, 0), (1, 1), (63, 1), (64, 1), (65, 2), (200, 4), (256, 4), (4096, 64), (4608, 72)]:
+        assert L.bnn_packed_words(K) == w
+    assert L.bnn_conv_kwords(128, 3, 3) == 18
+    assert L.bnn_conv_kwords(256, 3, 3) == 36
+    assert L.bnn_conv_kwords(200, 1, 1) == 4
+    assert L.bnn_conv_kwords(0, 3, 3) == 0
+    assert L.bnn_conv_out_dim(32, 3, 1, 1) == 32
+    assert L.bnn_conv_out_dim(56, 1, 2, 0) == 28
+    assert L.bnn_conv_out_dim(7, 3, 2, 1) == 4
+    assert L.bnn_conv_out_dim(2, 5, 1, 1) == 0
+    assert L.bnn_conv_out_dim(5, 3, 0, 0) == 0
+    # workspaces: packed NHWC image (+ patch matrix), each rounded up to 256 bytes
+    img = 128 * 32 * 32 * 2 * 8
+    assert L.bnn_im2col_workspace_bytes(128, 128, 32, 32, 3, 3, 1, 1, 1, 1) == img
+    assert L.bnn_conv2d_workspace_bytes(128, 128, 32, 32, 3, 3, 1, 1, 1, 1) == img + 131072 * 18 * 8
+    assert L.bnn_im2col_workspace_bytes(64, 200, 56, 56, 1, 1, 2, 2, 0, 0) == 0
+    assert L.bnn_conv2d_workspace_bytes(64, 200, 56, 56, 1, 1, 2, 2, 0, 0) == 50176 * 4 * 8
+    assert L.bnn_conv2d_workspace_bytes(1, 3, 2, 2, 5, 5, 1, 1, 0, 0) == 0  # invalid geometry
+
+
+A16 = 4096  # a fake, 16-byte aligned, never dereferenced address
+MIS = 4100  # misaligned
+
+
+def test_encode_errors(L):
+    assert L.bnn_encode(A16, -1, 8, 8, A16, 1, None) == SHAPE
+    assert L.bnn_encode(A16, 4, 0, 8, A16, 1, None) == SHAPE
+    assert L.bnn_encode(A16, 4, 65, 64, A16, 2, None) == STRIDE
+    assert L.bnn_encode(A16, 4, 65, 65, A16, 1, None) == STRIDE
+    assert L.bnn_encode(None, 0, 8, 8, None, 1, None) == OK  # empty: nothing to do
+    assert L.bnn_encode(None, 4, 8, 8, A16, 1, None) == NULL
+    assert L.bnn_encode(A16, 4, 8, 8, None, 1, None) == NULL
+    assert L.bnn_encode(MIS, 4, 8, 8, A16, 1, None) == ALIGN
+    assert L.bnn_encode(A16, 4, 8, 8, MIS, 1, None) == ALIGN
+
+
+def test_pack_conv_weight_errors(L):
+    assert L.bnn_pack_conv_weight(A16, 4, 0, 3, 3, A16, None) == SHAPE
+    assert L.bnn_pack_conv_weight(A16, -1, 8, 3, 3, A16, None) == SHAPE
+    assert L.bnn_pack_conv_weight(None, 0, 8, 3, 3, None, None) == OK
+    assert L.bnn_pack_conv_weight(None, 4, 8, 3, 3, A16, None) == NULL
+    assert L.bnn_pack_conv_weight(A16, 4, 8, 3, 3, MIS, None) == ALIGN
+
+
+def test_gemm_errors(L):
+    g = L.bnn_xnor_gemm
+    assert g(A16, 4, A16, 4, A16, 8, 8, 8, 0, None) == SHAPE
+    assert g(A16, 4, A16, 4, A16, 8, -1, 8, 256, None) == SHAPE
+    assert g(A16, 3, A16, 4, A16, 8, 8, 8, 256, None) == STRIDE
+    assert g(A16, 4, A16, 3, A16, 8, 8, 8, 256, None) == STRIDE
+    assert g(A16, 4, A16, 4, A16, 7, 8, 8, 256, None) == STRIDE
+    assert g(None, 4, None, 4, None, 8, 0, 8, 256, None) == OK
+    assert g(None, 4, None, 4, None, 8, 8, 0, 256, None) == OK
+    assert g(None, 4, A16, 4, A16, 8, 8, 8, 256, None) == NULL
+    assert g(A16, 4, A16, 4, None, 8, 8, 8, 256, None) == NULL
+    assert g(A16, 4, MIS, 4, A16, 8, 8, 8, 256, None) == ALIGN
+    e = L.bnn_xnor_gemm_epilogue
+    assert e(A16, 4, A16, 4, 8, 8, 256, None, 8, None, 8, None, None, 0, None) == NULL  # no output at all
+    assert e(A16, 4, A16, 4, 8, 8, 256, None, 8, A16, 8, None, A16, 1, None) == NULL  # Y without scale
+    assert e(A16, 4, A16, 4, 8, 8, 256, None, 8, A16, 8, A16, A16, 0, None) == SHAPE  # Y needs an axis
+    assert e(A16, 4, A16, 4, 8, 8, 256, None, 8, A16, 7, A16, A16, 1, None) == STRIDE
+    assert e(A16, 4, A16, 4, 8, 8, 256, MIS, 8, A16, 8, A16, A16, 1, None) == ALIGN
+
+
+def test_conv_and_im2col_errors(L):
+    geo = (2, 8, 6, 6, 3, 3, 1, 1, 1, 1)
+    need = L.bnn_conv2d_workspace_bytes(*geo)
+    need_i = L.bnn_im2col_workspace_bytes(*geo)
+    assert need > need_i > 0
+    im = L.bnn_im2col_packed
+    assert im(A16, 2, 8, 6, 6, 7, 7, 1, 1, 0, 0, A16, A16, 1 << 20, None) == SHAPE  # OH < 1
+    assert im(A16, 2, 8, 6, 6, 3, 3, 0, 1, 1, 1, A16, A16, 1 << 20, None) == SHAPE  # stride 0
+    assert im(A16, 2, 0, 6, 6, 3, 3, 1, 1, 1, 1, A16, A16, 1 << 20, None) == SHAPE
+    assert im(None, 0, 8, 6, 6, 3, 3, 1, 1, 1, 1, None, None, 0, None) == OK
+    assert im(None, *geo, A16, A16, need_i, None) == NULL
+    assert im(A16, *geo, A16, None, need_i, None) == NULL
+    assert im(A16, *geo, MIS, A16, need_i, None) == ALIGN
+    assert im(A16, *geo, A16, A16, need_i - 1, None) == WORKSPACE
+    cv = L.bnn_conv2d
+    base = dict(x=A16, w=A16, oi=A16, of=None, sc=None, bi=None, ws=A16, wb=need)
+
+    def call(D=4, g=geo, **kw):
+        a = dict(base, **kw)
+        N, C, H, W, kH, kW, sH, sW, pH, pW = g
+        return cv(a["x"], a["w"], N, C, H, W, D, kH, kW, sH, sW, pH, pW, a["oi"], a["of"], a["sc"], a["bi"], a["ws"],
+                  a["wb"], None)
+
+    assert call(g=(2, 8, 6, 6, 3, 3, 1, 1, -1, 1)) == SHAPE
+    assert call(D=-1) == SHAPE
+    assert call(D=0) == OK
+    assert call(x=None) == NULL
+    assert call(oi=None) == NULL  # neither output
+    assert call(of=A16) == NULL  # fp32 output without scale / bias
+    assert call(ws=None) == NULL
+    assert call(w=MIS) == ALIGN
+    assert call(wb=need - 1) == WORKSPACE
+
+
+def test_glue_errors(L):
+    mp = L.bnn_maxpool2x2
+    assert mp(A16, 2, 4, 5, 6, A16, None, None, None, None) == SHAPE  # odd H
+    assert mp(A16, 2, 4, 6, 6, None, None, None, None, None) == NULL
+    assert mp(A16, 2, 4, 6, 6, None, A16, None, None, None) == NULL
+    assert mp(MIS, 2, 4, 6, 6, A16, None, None, None, None) == ALIGN
+    assert mp(None, 0, 4, 6, 6, None, None, None, None, None) == OK
+    cf = L.bnn_conv2d_f32
+    assert cf(A16, A16, 2, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1, A16, None, A16, None) == NULL  # scale without bias
+    assert cf(A16, A16, 2, 3, 8, 8, 4, 9, 9, 1, 1, 0, 0, None, None, A16, None) == SHAPE
+    assert cf(A16, None, 2, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1, None, None, A16, None) == NULL
+    fc = L.bnn_fc_f32
+    assert fc(A16, A16, None, 4, 0, 4, 0, A16, None) == SHAPE
+    assert fc(A16, A16, None, 4, 8, 4, 0, None, None) == NULL
+    assert fc(A16, MIS, None, 4, 8, 4, 0, A16, None) == ALIGN
+    assert L.bnn_valu_peak_probe(None, 4, 4, None) == NULL
+    assert L.bnn_valu_peak_probe(A16, -1, 4, None) == SHAPE
+    assert L.bnn_copy_probe(A16, A16, 24, None) == SHAPE
+    assert L.bnn_copy_probe(A16, None, 32, None) == NULL
+
+
+def test_prof_hook_is_inert_without_launches(L):
+    assert L.bnn_prof_count() == 0
+    assert L.bnn_prof_reset() == OK
+    assert L.bnn_kernel_name(4).decode() == "xnor_gemm"
+    assert L.bnn_kernel_name(1234).decode() == "unknown"

@@ -1,0 +1,341 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle, element by element,
+on the same seeded host-generated inputs.  Integer / packed outputs must be bit-exact;
+the fp32 epilogue must match within 1e-6 relative (it is in fact built to be bit-exact)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1911_04477_amd import binding as B
+from paper_1911_04477_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def as_u64(t):
+    return host(t).view("<u8")
+
+
+def assert_f32_close(got, ref):
+    assert got.shape == ref.shape
+    # 1e-6 relative, as the contract asks; report bit-exactness too
+    assert np.allclose(got, ref, rtol=1e-6, atol=1e-30), np.abs(got - ref).max()
+
+
+# ---------------------------------------------------------------- encode (a1)
+@pytest.mark.parametrize("rows,K", [(1, 1), (3, 31), (5, 64), (7, 65), (64, 256), (33, 200), (2, 4097), (130, 1152),
+                                     (1000, 63), (17, 1024 + 13)])
+def test_encode_matches_oracle(rows, K):
+    print(f"encode rows={rows} K={K}", flush=True)
+    rng = np.random.default_rng(rows * 100003 + K)
+    x = inputs.inject_specials(rng.standard_normal((rows, K)).astype(np.float32), K, frac=0.01)
+    got = as_u64(B.bnn_encode(dev(x)))
+    assert np.array_equal(got, oracle.encode_rows(x))
+
+
+def test_encode_strided_src_and_dst():
+    print("encode strided", flush=True)
+    rng = np.random.default_rng(5)
+    rows, K, sld, dld = 37, 130, 140, 5
+    big = rng.standard_normal((rows, sld)).astype(np.float32)
+    src = dev(big)[:, :K]
+    dst = torch.full((rows, dld), -1, dtype=torch.int64, device=DEV)
+    B.bnn_encode(src, dst[:, :3])
+    out = as_u64(dst)
+    assert np.array_equal(out[:, :3], oracle.encode_rows(big[:, :K]))
+    assert np.all(out[:, 3:] == np.uint64(0xFFFFFFFFFFFFFFFF))  # words past Kw untouched
+
+
+def test_encode_cfg2_weights_full_size():
+    print("encode cfg2 weights 4096x4096", flush=True)
+    d = inputs.cfg2()
+    got = as_u64(B.bnn_encode(dev(d["wt"])))
+    assert np.array_equal(got, oracle.encode_rows(d["wt"]))
+
+
+# ---------------------------------------------------------------- weight packing / im2col (a2)
+CONV_CASES = [
+    # N, C, H, W, D, kH, kW, sH, sW, pH, pW
+    (2, 64, 6, 6, 5, 3, 3, 1, 1, 1, 1),
+    (2, 128, 9, 7, 33, 3, 3, 1, 1, 1, 1),
+    (3, 70, 8, 8, 9, 3, 3, 2, 2, 1, 1),
+    (2, 200, 10, 10, 17, 1, 1, 2, 2, 0, 0),
+    (1, 3, 12, 12, 4, 5, 5, 1, 1, 2, 2),
+    (2, 256, 5, 6, 70, 3, 3, 1, 1, 0, 0),
+    (1, 130, 7, 9, 3, 3, 1, 1, 2, 1, 0),
+    (5, 192, 4, 4, 130, 1, 1, 1, 1, 0, 0),
+    (1, 512, 8, 8, 12, 3, 3, 1, 1, 1, 1),
+    (2, 32, 6, 5, 6, 2, 2, 1, 1, 1, 1),
+    (1, 1, 3, 3, 1, 3, 3, 1, 1, 1, 1),
+]
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_pack_weight_and_im2col_match_oracle(case):
+    print(f"im2col case={case}", flush=True)
+    N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
+    rng = np.random.default_rng(sum(case))
+    x = inputs.inject_specials(rng.standard_normal((N, C, H, W)).astype(np.float32), 1, frac=0.01)
+    w = inputs.inject_specials(rng.standard_normal((D, C, kH, kW)).astype(np.float32), 2, frac=0.01)
+    assert np.array_equal(as_u64(B.bnn_pack_conv_weight(dev(w))), oracle.pack_conv_weight(w))
+    cols = as_u64(B.bnn_im2col_packed(dev(x), kH, kW, (sH, sW), (pH, pW)))
+    assert np.array_equal(cols, oracle.im2col_packed(x, kH, kW, (sH, sW), (pH, pW)))
+
+
+# ---------------------------------------------------------------- GEMM (a3)
+def _gemm_case(M, N, K, seed, cfg=None):
+    rng = np.random.default_rng(seed)
+    A = inputs.inject_specials(rng.standard_normal((M, K)).astype(np.float32), seed, frac=0.002)
+    Bm = inputs.inject_specials(rng.standard_normal((N, K)).astype(np.float32), seed + 1, frac=0.002)
+    Ap, Bp = B.bnn_encode(dev(A)), B.bnn_encode(dev(Bm))
+    got = host(B.bnn_xnor_gemm(Ap, Bp, K))
+    assert np.array_equal(got, oracle.gemm_pm1(A, Bm))
+
+
+@pytest.mark.parametrize("K", [1, 31, 32, 33, 63, 64, 65, 200, 256, 257, 511, 512, 544, 1152, 2304 + 17])
+@pytest.mark.parametrize("cfg", [0, 1, 2])
+def test_gemm_k_sweep_all_tile_configs(K, cfg):
+    print(f"gemm K={K} cfg={cfg}", flush=True)
+    B.lib().bnn_internal_force_gemm_cfg(cfg)
+    try:
+        _gemm_case(37, 150, K, seed=K * 7 + cfg)
+    finally:
+        B.lib().bnn_internal_force_gemm_cfg(-1)
+
+
+@pytest.mark.parametrize("M,N", [(1, 1), (1, 700), (65, 513), (64, 512), (130, 1030), (257, 64), (33, 65)])
+@pytest.mark.parametrize("cfg", [0, 1, 2])
+def test_gemm_ragged_tiles(M, N, cfg):
+    print(f"gemm M={M} N={N} cfg={cfg}", flush=True)
+    B.lib().bnn_internal_force_gemm_cfg(cfg)
+    try:
+        _gemm_case(M, N, 300, seed=M * 1000 + N + cfg)
+    finally:
+        B.lib().bnn_internal_force_gemm_cfg(-1)
+
+
+def test_gemm_table1_truth_table():
+    """Table 1 of the paper through encode + GEMM with K = 1 (63 masked tail bits)."""
+    print("gemm truth table", flush=True)
+    vals = np.array([[-1.0], [1.0]], dtype=np.float32)
+    P = B.bnn_encode(dev(vals))
+    assert as_u64(P).reshape(-1).tolist() == [0, 1]
+    got = host(B.bnn_xnor_gemm(P, P, 1))
+    assert got.tolist() == [[1, -1], [-1, 1]]
+
+
+def test_gemm_masks_garbage_past_K():
+    print("gemm tail garbage", flush=True)
+    rng = np.random.default_rng(11)
+    for K in (1, 33, 70, 200):
+        A = rng.standard_normal((9, K)).astype(np.float32)
+        Bm = rng.standard_normal((70, K)).astype(np.float32)
+        Ap, Bp = as_u64(B.bnn_encode(dev(A))).copy(), as_u64(B.bnn_encode(dev(Bm))).copy()
+        tail = K % 64
+        garbage = np.uint64((0xFFFFFFFFFFFFFFFF >> tail) << tail) if tail else np.uint64(0)
+        Ap[:, -1] |= garbage & np.uint64(0xA5A5A5A5A5A5A5A5)
+        Bp[:, -1] |= garbage & np.uint64(0x0F0F0F0FF0F0F0F0)
+        got = host(B.bnn_xnor_gemm(dev(Ap.view(np.int64)), dev(Bp.view(np.int64)), K))
+        assert np.array_equal(got, oracle.gemm_pm1(A, Bm)), K
+
+
+def test_gemm_leading_dimensions():
+    print("gemm ld", flush=True)
+    rng = np.random.default_rng(12)
+    M, N, K = 20, 90, 330
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    Bm = rng.standard_normal((N, K)).astype(np.float32)
+    Kw = B.packed_words(K)
+    Abig = torch.full((M, Kw + 3), 0x5555, dtype=torch.int64, device=DEV)
+    Bbig = torch.full((N, Kw + 1), 0x3333, dtype=torch.int64, device=DEV)  # odd ldb: 8-byte load path
+    B.bnn_encode(dev(A), Abig[:, :Kw])
+    B.bnn_encode(dev(Bm), Bbig[:, :Kw])
+    Cbig = torch.full((M, N + 5), -7, dtype=torch.int32, device=DEV)
+    B.bnn_xnor_gemm(Abig[:, :Kw], Bbig[:, :Kw], K, Cbig[:, :N])
+    out = host(Cbig)
+    assert np.array_equal(out[:, :N], oracle.gemm_pm1(A, Bm))
+    assert np.all(out[:, N:] == -7)
+
+
+def test_gemm_deterministic_twice():
+    print("gemm determinism", flush=True)
+    d = inputs.cfg1()
+    Ap, Bp = B.bnn_encode(dev(d["A"])), B.bnn_encode(dev(d["B"]))
+    a = host(B.bnn_xnor_gemm(Ap, Bp, inputs.CFG1.K))
+    b = host(B.bnn_xnor_gemm(Ap, Bp, inputs.CFG1.K))
+    assert np.array_equal(a, b)
+
+
+# ---------------------------------------------------------------- the five configurations
+def test_cfg1_single_gemm():
+    print("cfg1", flush=True)
+    d = inputs.cfg1()
+    A = inputs.inject_specials(d["A"], 1)
+    Bm = inputs.inject_specials(d["B"], 2)
+    Ap, Bp = B.bnn_encode(dev(A)), B.bnn_encode(dev(Bm))
+    assert as_u64(Ap).view("<u4").shape == (64, 8)
+    assert np.array_equal(host(B.bnn_xnor_gemm(Ap, Bp, 256)), oracle.gemm_pm1(A, Bm))
+
+
+def test_cfg2_fc_layer_full_size():
+    print("cfg2", flush=True)
+    d = inputs.cfg2()
+    act = inputs.inject_specials(d["act"], 3)
+    Ap, Wp = B.bnn_encode(dev(act)), B.bnn_encode(dev(d["wt"]))
+    C, Y = B.bnn_xnor_gemm_epilogue(Ap, Wp, inputs.CFG2.K, dev(d["scale"]), dev(d["bias"]), B.CH_COL, want_int=True)
+    ref = oracle.gemm_pm1(act, d["wt"])
+    assert np.array_equal(host(C), ref)
+    yref = oracle.scale_bias(ref, d["scale"], d["bias"], "col")
+    got = host(Y)
+    assert_f32_close(got, yref)
+    assert np.array_equal(got, yref)  # single-rounded fma on both sides: bit-exact
+
+
+def _conv_parity(shape, data, full=True, n_samples=200_000, with_epilogue=True):
+    x = inputs.inject_specials(data["x"], 7, frac=1e-4)
+    w = data["w"]
+    xd, wd = dev(x), dev(w)
+    wp = B.bnn_pack_conv_weight(wd)
+    st, pd = (shape.sH, shape.sW), (shape.pH, shape.pW)
+    sc, bi = dev(data["scale"]), dev(data["bias"])
+    oi, of = B.bnn_conv2d(xd, wp, shape.D, shape.kH, shape.kW, st, pd, sc if with_epilogue else None,
+                          bi if with_epilogue else None, want_int=True)
+    got = host(oi)
+    assert got.shape == (x.shape[0], shape.D, shape.OH, shape.OW)
+    if full:
+        ref = oracle.conv2d_pm1(x, w, st, pd)
+        assert np.array_equal(got, ref)
+        if with_epilogue:
+            yref = oracle.scale_bias(ref, data["scale"], data["bias"], "nchw")
+            assert_f32_close(host(of), yref)
+            assert np.array_equal(host(of), yref)
+    else:
+        rng = np.random.default_rng(99)
+        idx = np.unique(np.concatenate([rng.integers(0, got.size, n_samples), np.arange(0, 4096),
+                                        np.arange(got.size - 4096, got.size)]))
+        ref = oracle.conv2d_pm1_at(x, w, idx, st, pd)
+        assert np.array_equal(got.reshape(-1)[idx], ref)
+        # properties that hold for every output, at any size
+        K = shape.K
+        assert np.all((got - K) % 2 == 0) and np.all(np.abs(got) <= K)
+        if with_epilogue:
+            ch = (idx // (shape.OH * shape.OW)) % shape.D
+            yref = np.array([np.float32(np.float64(data["scale"][c]) * float(v) + np.float64(data["bias"][c]))
+                             for c, v in zip(ch[:2000], ref[:2000])], dtype=np.float32)
+            assert_f32_close(host(of).reshape(-1)[idx[:2000]], yref)
+
+
+def test_cfg3_cifar_conv_full_size():
+    print("cfg3", flush=True)
+    _conv_parity(inputs.CFG3, inputs.cfg3(), full=True)
+
+
+def test_cfg5a_imagenet_conv_sampled():
+    print("cfg5a", flush=True)
+    _conv_parity(inputs.CFG5A, inputs.cfg5a(), full=False)
+
+
+def test_cfg5b_ragged_k_pointwise_stride2_full_size():
+    print("cfg5b", flush=True)
+    _conv_parity(inputs.CFG5B, inputs.cfg5b(), full=True)
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv2d_small_cases(case):
+    print(f"conv case={case}", flush=True)
+    N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
+    shape = inputs.ConvShape(N, C, H, W, D, kH, kW, sH, sW, pH, pW)
+    _conv_parity(shape, inputs.conv_inputs(shape, seed=sum(case)), full=True)
+
+
+def test_conv2d_worked_examples():
+    print("conv worked examples", flush=True)
+    x = torch.full((1, 1, 3, 3), -1.0, device=DEV)
+    w = torch.full((1, 1, 3, 3), 1.0, device=DEV)
+    oi, _ = B.bnn_conv2d(x, B.bnn_pack_conv_weight(w), 1, 3, 3, (1, 1), (1, 1))
+    assert host(oi)[0, 0].tolist() == [[1, -3, 1], [-3, -9, -3], [1, -3, 1]]
+    x = torch.tensor([[[[1.0, -1.0], [-1.0, 1.0]]]], device=DEV)
+    w = torch.tensor([[[[1.0, -1.0, 1.0], [-1.0, 1.0, -1.0], [1.0, -1.0, 1.0]]]], device=DEV)
+    oi, _ = B.bnn_conv2d(x, B.bnn_pack_conv_weight(w), 1, 3, 3, (1, 1), (1, 1))
+    assert host(oi)[0, 0].tolist() == [[5, -3], [-3, 5]]
+
+
+# ---------------------------------------------------------------- glue (a6) and the stack (cfg 4)
+def test_maxpool_and_f32_glue():
+    print("glue", flush=True)
+    rng = np.random.default_rng(21)
+    a = rng.integers(-1152, 1153, size=(3, 5, 8, 6)).astype(np.int32)
+    sc = (rng.random(5) + 0.5).astype(np.float32)
+    bi = (rng.standard_normal(5) * 0.1).astype(np.float32)
+    oi, of = B.bnn_maxpool2x2(dev(a), dev(sc), dev(bi), want_int=True)
+    ref = oracle.maxpool2x2_i32(a)
+    assert np.array_equal(host(oi), ref)
+    assert np.array_equal(host(of), oracle.scale_bias(ref, sc, bi, "nchw"))
+    x = rng.standard_normal((3, 3, 9, 8)).astype(np.float32)
+    w = rng.standard_normal((5, 3, 3, 3)).astype(np.float32)
+    got = host(B.bnn_conv2d_f32(dev(x), dev(w), (1, 1), (1, 1), dev(sc), dev(bi)))
+    assert np.array_equal(got, oracle.conv2d_f32_seq(x, w, (1, 1), (1, 1), sc, bi))
+    got = host(B.bnn_conv2d_f32(dev(x), dev(w), (2, 1), (0, 1)))
+    assert np.array_equal(got, oracle.conv2d_f32_seq(x, w, (2, 1), (0, 1)))
+    xf = rng.standard_normal((6, 100)).astype(np.float32)
+    wf = rng.standard_normal((10, 100)).astype(np.float32)
+    bf = rng.standard_normal(10).astype(np.float32)
+    for sgn in (False, True):
+        got = host(B.bnn_fc_f32(dev(xf), dev(wf), dev(bf), sign_input=sgn))
+        assert np.array_equal(got, oracle.fc_f32_seq(xf, wf, bf, sign_input=sgn))
+
+
+@pytest.mark.parametrize("reading", ["A", "B"])
+def test_cfg4_stack_small_batch_every_layer(reading):
+    print(f"cfg4 stack batch 4 reading {reading}", flush=True)
+    from paper_1911_04477_amd.stack import VggStack
+    d = inputs.cfg4(batch=4, reading=reading)
+    net = VggStack(d["layers"], d["params"], batch=4, device=DEV)
+    out, acts = net.forward(dev(d["x"]), keep=True)
+    ref = oracle.vgg_stack(d["x"], d["layers"], d["params"])
+    for i, (g, r) in enumerate(zip(acts, ref["acts"])):
+        assert np.array_equal(host(g).reshape(r.shape), r), f"layer {i} ({d['layers'][i].kind})"
+    assert np.array_equal(host(out), ref["out"])
+
+
+def test_cfg4_stack_full_batch_sampled_images():
+    """Batch 256 as benchmarked; the oracle runs the stack on a few images (images are
+    independent units) and those rows must match bit for bit."""
+    print("cfg4 stack batch 256", flush=True)
+    from paper_1911_04477_amd.stack import VggStack
+    d = inputs.cfg4(batch=256)
+    net = VggStack(d["layers"], d["params"], batch=256, device=DEV)
+    out = host(net.forward(dev(d["x"])))
+    pick = [0, 101, 255]
+    ref = oracle.vgg_stack(d["x"][pick], d["layers"], d["params"])
+    assert np.array_equal(out[pick], ref["out"])
+    out2 = host(net.forward(dev(d["x"])))
+    assert np.array_equal(out, out2)
+
+
+# ---------------------------------------------------------------- timing hook
+def test_prof_hook_records_kernels():
+    print("prof hook", flush=True)
+    d = inputs.cfg1()
+    B.prof_enable(True)
+    try:
+        Ap, Bp = B.bnn_encode(dev(d["A"])), B.bnn_encode(dev(d["B"]))
+        B.bnn_xnor_gemm(Ap, Bp, 256)
+        rec = B.prof_records()
+        assert [r[0] for r in rec] == ["encode_rows", "encode_rows", "xnor_gemm_small"]
+        assert all(0.0 < r[1] < 50.0 for r in rec)
+        B.prof_reset()
+        assert B.prof_records() == []
+    finally:
+        B.prof_enable(False)
