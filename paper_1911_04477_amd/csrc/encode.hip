@@ -32,14 +32,18 @@ __global__ __launch_bounds__(ENC_BLOCK) void encode_rows_kernel(const float *__r
   int64_t row = g0 / Kw;
   int64_t w = g0 - row * Kw;
 
-  // Issue all loads first (independent), then compare.
+  // Issue all 16 loads back to back, unconditionally: a lane that has nothing to read
+  // (past K in the last word of a row, or past the last row) re-reads element 0 and is
+  // masked out afterwards.  Conditional loads would each wait for the previous one.
   float v[ENC_WORDS_PER_WAVE];
+  uint32_t okbits = 0;
   int64_t r = row, ww = w;
 #pragma unroll
   for (int u = 0; u < ENC_WORDS_PER_WAVE; ++u) {
     const int64_t k = ww * 64 + lane;
     const bool ok = (g0 + u < total_words) && (k < K);
-    v[u] = ok ? src[r * src_ld + k] : -1.0f;
+    okbits |= (uint32_t)ok << u;
+    v[u] = src[ok ? r * src_ld + k : 0];
     if (++ww == Kw) {
       ww = 0;
       ++r;
@@ -48,7 +52,7 @@ __global__ __launch_bounds__(ENC_BLOCK) void encode_rows_kernel(const float *__r
   uint64_t mine = 0;
 #pragma unroll
   for (int u = 0; u < ENC_WORDS_PER_WAVE; ++u) {
-    const uint64_t m = __ballot(sign_bit(v[u]));
+    const uint64_t m = __ballot(((okbits >> u) & 1u) && sign_bit(v[u]));
     if (lane == u) mine = m;
   }
   const int64_t g = g0 + lane;

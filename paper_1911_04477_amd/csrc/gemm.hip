@@ -32,6 +32,14 @@ typedef u32x4 u32x4_a8 __attribute__((aligned(8)));
 typedef const uint32_t BNN_CONST_AS *cu32_ptr;
 typedef const u32x4_a8 BNN_CONST_AS *cu32x4_ptr;
 
+using u32x8 = uint32_t __attribute__((ext_vector_type(8)));
+
+// acc += popcount(a ^ b): exactly two VALU instructions, a from an SGPR.
+__device__ __forceinline__ void xor_popc_acc(int &acc, uint32_t a_sgpr, uint32_t b) {
+  uint32_t t;
+  asm("v_xor_b32 %1, %2, %3\n\tv_bcnt_u32_b32 %0, %1, %0" : "+v"(acc), "=&v"(t) : "s"(a_sgpr), "v"(b));
+}
+
 // acc += popcount(x) as ONE instruction.  Written as asm because the optimizer otherwise
 // re-associates a chain of popcount-adds into v_bcnt(x, 0) plus separate three-operand adds,
 // which costs 25 % more VALU instructions in the inner loop.
@@ -46,19 +54,25 @@ struct GemmCfg {
   static constexpr int BN = 64 * TN * WN;
   static constexpr int THREADS = 64 * WM * WN;
   static constexpr int RS = KC + 4;                      // LDS row stride in dwords
+  static constexpr int TILE = BN * RS;                   // dwords per LDS buffer
   static constexpr int PIECES = BN * (KC / 4);           // 16-byte pieces per chunk
   static constexpr int PPT = (PIECES + THREADS - 1) / THREADS;
   static_assert(KC % 4 == 0, "chunk must be whole 16-byte pieces");
-  static_assert(PIECES % THREADS == 0, "staging must divide evenly");
+  static_assert(PIECES % THREADS == 0 || PIECES < THREADS, "staging must divide evenly");
 };
 
-template <int TM, int TN, int WM, int WN, int KC, int MINB>
-__global__ __launch_bounds__(64 * WM * WN, MINB) void xnor_gemm_kernel(GemmParams p) {
+// s_waitcnt lgkmcnt(0) only (vmcnt / expcnt left at their maxima).
+#define BNN_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
+#define BNN_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+template <int TM, int TN, int WM, int WN, int KC, int MINW>
+__global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParams p) {
   using Cfg = GemmCfg<TM, TN, WM, WN, KC>;
   constexpr int RS = Cfg::RS;
   constexpr int PPT = Cfg::PPT;
-  constexpr int QPR = KC / 4;  // pieces per row
-  __shared__ __attribute__((aligned(16))) uint32_t sB[Cfg::BN * RS];
+  constexpr int QPR = KC / 4;   // 16-byte pieces per row
+  constexpr int NSUB = KC / 4;  // sub-steps (4 dwords each) per chunk
+  __shared__ __attribute__((aligned(16))) uint32_t sB[2 * Cfg::TILE];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -95,12 +109,15 @@ __global__ __launch_bounds__(64 * WM * WN, MINB) void xnor_gemm_kernel(GemmParam
     for (int j = 0; j < TN; ++j) acc[i][j] = 0;
 
   const int nchunks = (p.Kd + KC - 1) / KC;
-  const int full_chunks = p.Kbits / (32 * KC);  // chunks whose every bit takes part
+  const int kd_full = p.Kbits >> 5;     // dwords whose 32 bits all take part
+  const int nsub_total = kd_full >> 2;  // mask-free sub-steps over the whole K range
   const int last_w = p.Kw64 - 1;
   const int tail_bits = p.Kbits & 63;
   const uint64_t tail_mask = tail_bits ? ((1ull << tail_bits) - 1ull) : ~0ull;
 
-  // ---- staging: global -> registers -> LDS --------------------------------------
+  // ---- staging: global -> registers -> LDS (double-buffered) -----------------------
+  // stage_load only ISSUES the global loads (raw words stay in registers, nothing uses them
+  // until stage_store a whole chunk of compute later), so their latency is never waited on.
   u32x4 stage[PPT];
   auto stage_load = [&](int chunk) {
 #pragma unroll
@@ -110,79 +127,148 @@ __global__ __launch_bounds__(64 * WM * WN, MINB) void xnor_gemm_kernel(GemmParam
       const int n = n0 + row;
       const int w0 = chunk * (KC / 2) + 2 * q;
       u32x4 v = {0u, 0u, 0u, 0u};
-      if (n < p.N && w0 <= last_w) {
+      if (idx < Cfg::PIECES && n < p.N && w0 <= last_w) {
         const uint64_t *src = p.B + (int64_t)n * p.ldb + w0;
-        uint64_t x0, x1 = 0;
         if (p.b_vec16 && w0 + 1 <= last_w) {
-          const u32x4 raw = *reinterpret_cast<const u32x4 *>(src);
-          x0 = ((uint64_t)raw.y << 32) | raw.x;
-          x1 = ((uint64_t)raw.w << 32) | raw.z;
+          v = *reinterpret_cast<const u32x4 *>(src);
         } else {
-          x0 = src[0];
-          if (w0 + 1 <= last_w) x1 = src[1];
+          const uint2 lo = *reinterpret_cast<const uint2 *>(src);
+          v.x = lo.x; v.y = lo.y;
+          if (w0 + 1 <= last_w) {
+            const uint2 hi = *reinterpret_cast<const uint2 *>(src + 1);
+            v.z = hi.x; v.w = hi.y;
+          }
         }
-        if (w0 == last_w) x0 &= tail_mask;
-        if (w0 + 1 == last_w) x1 &= tail_mask;
-        v.x = (uint32_t)x0; v.y = (uint32_t)(x0 >> 32); v.z = (uint32_t)x1; v.w = (uint32_t)(x1 >> 32);
       }
       stage[t] = v;
     }
   };
-  auto stage_store = [&]() {
+  // Masks the bits past K in the row's last word, then writes the pieces to LDS buffer buf.
+  auto stage_store = [&](int buf, int chunk) {
+    const uint32_t tm_lo = (uint32_t)tail_mask, tm_hi = (uint32_t)(tail_mask >> 32);
 #pragma unroll
     for (int t = 0; t < PPT; ++t) {
       const int idx = t * Cfg::THREADS + tid;
       const int row = idx / QPR, q = idx % QPR;
-      *reinterpret_cast<u32x4 *>(&sB[row * RS + q * 4]) = stage[t];
+      const int w0 = chunk * (KC / 2) + 2 * q;
+      u32x4 v = stage[t];
+      if (w0 == last_w) { v.x &= tm_lo; v.y &= tm_hi; }
+      if (w0 + 1 == last_w) { v.z &= tm_lo; v.w &= tm_hi; }
+      if (idx < Cfg::PIECES) *reinterpret_cast<u32x4 *>(&sB[buf * Cfg::TILE + row * RS + q * 4]) = v;
     }
   };
 
-  const uint32_t *sBlane = &sB[(wn * 64 * TN + lane) * RS];
+  auto compute = [&](const u32x4 (&a)[TM], const u32x4 (&b)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        acc[i][j] = popc_acc(a[i].x ^ b[j].x, acc[i][j]);
+        acc[i][j] = popc_acc(a[i].y ^ b[j].y, acc[i][j]);
+        acc[i][j] = popc_acc(a[i].z ^ b[j].z, acc[i][j]);
+        acc[i][j] = popc_acc(a[i].w ^ b[j].w, acc[i][j]);
+      }
+  };
 
+  const int lane_row = (wn * 64 * TN + lane) * RS;
+
+  // Per chunk of KC = 8 dwords: the wave's TM rows of A arrive with TM scalar loads of 8
+  // dwords each (64 SGPRs), issued together with the first LDS reads of B; one wait; then
+  // 2 * TM * TN * 8 xor / popcount instructions with only the second sub-step's LDS reads
+  // in between.  The loads are inline asm so that their place in the instruction stream is
+  // fixed; the wait names every loaded register as in/out operand, which orders all uses
+  // after it.  The latency of one wave's loads is covered by the other resident waves.
+  static_assert(KC == 8 || TM * KC <= 64, "A chunk must fit the SGPR budget");
   stage_load(0);
-  for (int c = 0; c < nchunks; ++c) {
-    if (c > 0) __syncthreads();  // everyone is done reading the previous chunk
-    stage_store();
-    __syncthreads();
-    if (c + 1 < nchunks) stage_load(c + 1);
+  stage_store(0, 0);
+  __syncthreads();
 
-    const int kd0 = c * KC;
-    const cu32_ptr Ak = Ac + kd0;  // wave-uniform
-    // one sub-step: 4 dwords of every row against 4 dwords of every column, no masks
-    auto substep = [&](int s) {
-      u32x4 b[TN];
+  // 64-bit base of A in an SGPR pair (both halves made explicitly wave-uniform)
+  // (readfirstlane returns a signed int: each half is cast to unsigned before widening)
+  const uint32_t Abase_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)p.A);
+  const uint32_t Abase_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uintptr_t)p.A >> 32));
+  const uint64_t Abase = ((uint64_t)Abase_hi << 32) | (uint64_t)Abase_lo;
+  uint32_t aoffb[TM];  // byte offsets
 #pragma unroll
-      for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&sBlane[j * 64 * RS + s]);
+  for (int i = 0; i < TM; ++i) aoffb[i] = aoff[i] * 4u;
+
+  for (int c = 0; c < nchunks; ++c) {
+    const int buf = c & 1;
+    if (c + 1 < nchunks) stage_load(c + 1);
+    const uint32_t *sBl = &sB[buf * Cfg::TILE + lane_row];
+    const int sub0 = c * NSUB;                              // first sub-step index of this chunk
+    const int nsub = min(NSUB, max(nsub_total - sub0, 0));  // mask-free sub-steps in this chunk
+    const cu32_ptr Ak = Ac + c * KC;
+
+    if (nsub == NSUB) {
+      if constexpr (KC == 8) {
+        u32x8 a[TM];
+        u32x4 b[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const u32x4 a = *(cu32x4_ptr)(Ak + aoff[i] + s);
+        for (int i = 0; i < TM; ++i)
+          asm volatile("s_load_dwordx8 %0, %1, %2"
+                       : "=s"(a[i])
+                       : "s"(Abase), "s"((uint32_t)__builtin_amdgcn_readfirstlane((int)(aoffb[i] + (uint32_t)c * (KC * 4u)))));
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          acc[i][j] = popc_acc(a.x ^ b[j].x, acc[i][j]);
-          acc[i][j] = popc_acc(a.y ^ b[j].y, acc[i][j]);
-          acc[i][j] = popc_acc(a.z ^ b[j].z, acc[i][j]);
-          acc[i][j] = popc_acc(a.w ^ b[j].w, acc[i][j]);
+        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&sBl[j * 64 * RS]);
+        if constexpr (TM == 8)
+          asm volatile("s_waitcnt lgkmcnt(0)"
+                       : "+s"(a[0]), "+s"(a[1]), "+s"(a[2]), "+s"(a[3]), "+s"(a[4]), "+s"(a[5]), "+s"(a[6]),
+                         "+s"(a[7]));
+        else
+          static_assert(TM == 8, "wait statement is written for TM == 8");
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            xor_popc_acc(acc[i][j], a[i][0], b[j].x);
+            xor_popc_acc(acc[i][j], a[i][1], b[j].y);
+            xor_popc_acc(acc[i][j], a[i][2], b[j].z);
+            xor_popc_acc(acc[i][j], a[i][3], b[j].w);
+          }
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&sBl[j * 64 * RS + 4]);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            xor_popc_acc(acc[i][j], a[i][4], b[j].x);
+            xor_popc_acc(acc[i][j], a[i][5], b[j].y);
+            xor_popc_acc(acc[i][j], a[i][6], b[j].z);
+            xor_popc_acc(acc[i][j], a[i][7], b[j].w);
+          }
+      } else {
+#pragma unroll
+        for (int s = 0; s < NSUB; ++s) {
+          u32x4 a[TM], b[TN];
+#pragma unroll
+          for (int i = 0; i < TM; ++i) a[i] = *(cu32x4_ptr)(Ak + aoff[i] + 4 * s);
+#pragma unroll
+          for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&sBl[j * 64 * RS + 4 * s]);
+          compute(a, b);
         }
       }
-    };
-    if (c < full_chunks) {
-#pragma unroll
-      for (int s = 0; s < KC; s += 4) substep(s);
     } else {
-      // final partial chunk: whole mask-free sub-steps first, then one dword at a time.
-      // B is already masked / zero-filled by the staging; A is masked here.
-      const int kd_end = p.Kd < kd0 + KC ? p.Kd : kd0 + KC;  // dwords holding any bit
-      const int kd_full = p.Kbits >> 5;                       // dwords holding 32 bits
-      int s = 0;
 #pragma unroll 1
-      for (; kd0 + s + 4 <= kd_full; s += 4) substep(s);
+      for (int s = 0; s < nsub; ++s) {
+        u32x4 a[TM], b[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[i] = *(cu32x4_ptr)(Ak + aoff[i] + 4 * s);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&sBl[j * 64 * RS + 4 * s]);
+        compute(a, b);
+      }
+      // dwords past the last whole sub-step: one at a time, A masked here, B already masked
+      // and zero-filled by the staging.
+      const int kd0 = c * KC;
+      const int kd_end = p.Kd < kd0 + KC ? p.Kd : kd0 + KC;
       const int tb32 = p.Kbits & 31;
 #pragma unroll 1
-      for (int kd = kd0 + s; kd < kd_end; ++kd) {
+      for (int kd = kd0 + 4 * nsub; kd < kd_end; ++kd) {
         const uint32_t amask = (kd == p.Kd - 1 && tb32) ? ((1u << tb32) - 1u) : 0xffffffffu;
         uint32_t b[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[j] = sBlane[j * 64 * RS + (kd - kd0)];
+        for (int j = 0; j < TN; ++j) b[j] = sBl[j * 64 * RS + (kd - kd0)];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
           const uint32_t a = Ac[aoff[i] + kd] & amask;
@@ -190,6 +276,10 @@ __global__ __launch_bounds__(64 * WM * WN, MINB) void xnor_gemm_kernel(GemmParam
           for (int j = 0; j < TN; ++j) acc[i][j] = popc_acc(a ^ b[j], acc[i][j]);
         }
       }
+    }
+    if (c + 1 < nchunks) {
+      stage_store(buf ^ 1, c + 1);  // the other buffer was last read in chunk c-1, before the barrier below
+      __syncthreads();
     }
   }
 
@@ -244,7 +334,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINB) void xnor_gemm_kernel(GemmParam
 }
 
 // ---- host side ----------------------------------------------------------------------
-template <int TM, int TN, int WM, int WN, int KC, int MINB>
+template <int TM, int TN, int WM, int WN, int KC, int MINW>
 static bnn_status launch_cfg(GemmParams &p, hipStream_t s, int kid) {
   using Cfg = GemmCfg<TM, TN, WM, WN, KC>;
   p.tilesM = (p.M + Cfg::BM - 1) / Cfg::BM;
@@ -252,7 +342,7 @@ static bnn_status launch_cfg(GemmParams &p, hipStream_t s, int kid) {
   const int64_t blocks = (int64_t)p.tilesM * p.tilesN;
   if (blocks > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   ProfScope ps(kid, s);
-  hipLaunchKernelGGL((xnor_gemm_kernel<TM, TN, WM, WN, KC, MINB>), dim3((unsigned)blocks), dim3(Cfg::THREADS), 0, s,
+  hipLaunchKernelGGL((xnor_gemm_kernel<TM, TN, WM, WN, KC, MINW>), dim3((unsigned)blocks), dim3(Cfg::THREADS), 0, s,
                      p);
   return launch_status();
 }
@@ -263,14 +353,14 @@ int g_force_cfg = -1;  // test / tuning hook: -1 = heuristic
 // else but needs enough tiles to fill 256 CUs twice over; smaller problems fall back to
 // finer tiles so that every CU has work.
 bnn_status run_gemm(GemmParams &p, hipStream_t s) {
-  const int64_t tilesL = (int64_t)((p.M + 63) / 64) * ((p.N + 511) / 512);
+  const int64_t tilesL = (int64_t)((p.M + 31) / 32) * ((p.N + 511) / 512);
   const int64_t tilesMd = (int64_t)((p.M + 31) / 32) * ((p.N + 255) / 256);
   int cfg = g_force_cfg;
   if (cfg < 0) cfg = tilesL >= 512 ? 0 : (tilesMd >= 512 ? 1 : 2);
   switch (cfg) {
-    case 0: return launch_cfg<8, 8, 8, 1, 8, 1>(p, s, KID_XNOR_GEMM);
-    case 1: return launch_cfg<8, 4, 4, 1, 8, 2>(p, s, KID_XNOR_GEMM);
-    default: return launch_cfg<8, 1, 4, 1, 16, 2>(p, s, KID_XNOR_GEMM_SMALL);
+    case 0: return launch_cfg<8, 8, 4, 1, 8, 2>(p, s, KID_XNOR_GEMM);
+    case 1: return launch_cfg<8, 4, 4, 1, 8, 4>(p, s, KID_XNOR_GEMM);
+    default: return launch_cfg<8, 1, 4, 1, 8, 4>(p, s, KID_XNOR_GEMM_SMALL);
   }
 }
 

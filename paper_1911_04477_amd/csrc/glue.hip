@@ -29,65 +29,113 @@ __global__ __launch_bounds__(256) void maxpool2x2_kernel(const int32_t *__restri
   }
 }
 
+// One thread per output pixel, all D output channels in groups of CONV_DB accumulators.
+// Every output still sees its taps in the order (c, kh, kw), one fma each.  Within a
+// group the input value is loaded once and the weights are wave-uniform (scalar loads).
+constexpr int CONV_DB = 16;
 __global__ __launch_bounds__(256) void conv2d_f32_kernel(const float *__restrict__ x, const float *__restrict__ w,
                                                          int C, int H, int W, int D, int kH, int kW, int sH, int sW,
                                                          int pH, int pW, int OH, int OW,
                                                          const float *__restrict__ scale,
                                                          const float *__restrict__ bias, float *__restrict__ out,
-                                                         FastDiv divOW, FastDiv divOH, FastDiv divD, uint32_t total) {
-  const uint32_t o = blockIdx.x * 256u + threadIdx.x;
-  if (o >= total) return;
-  const uint32_t t = fdiv(o, divOW);
-  const uint32_t ow = o - t * OW;
-  const uint32_t t2 = fdiv(t, divOH);
-  const uint32_t oh = t - t2 * OH;
-  const uint32_t n = fdiv(t2, divD);
-  const uint32_t d = t2 - n * D;
-  float acc = 0.0f;
-  for (int c = 0; c < C; ++c)
-    for (int kh = 0; kh < kH; ++kh)
-      for (int kw = 0; kw < kW; ++kw) {
-        const int ih = (int)(oh * sH) + kh - pH, iw = (int)(ow * sW) + kw - pW;
-        float xv = 0.0f;
-        if (ih >= 0 && ih < H && iw >= 0 && iw < W) xv = x[(((size_t)n * C + c) * H + ih) * W + iw];
-        acc = fmaf(xv, w[(((size_t)d * C + c) * kH + kh) * kW + kw], acc);
+                                                         FastDiv divOW, FastDiv divOH, uint32_t total_pix) {
+  const uint32_t p = blockIdx.x * 256u + threadIdx.x;
+  if (p >= total_pix) return;
+  const uint32_t t = fdiv(p, divOW);
+  const uint32_t ow = p - t * OW;
+  const uint32_t n = fdiv(t, divOH);
+  const uint32_t oh = t - n * OH;
+  const int ih0 = (int)(oh * sH) - pH, iw0 = (int)(ow * sW) - pW;
+  const float *xn = x + (size_t)n * C * H * W;
+  const size_t opix = (size_t)oh * OW + ow;
+  const int taps = kH * kW;
+  for (int d0 = 0; d0 < D; d0 += CONV_DB) {
+    float acc[CONV_DB];
+#pragma unroll
+    for (int j = 0; j < CONV_DB; ++j) acc[j] = 0.0f;
+    for (int c = 0; c < C; ++c)
+      for (int kh = 0; kh < kH; ++kh)
+        for (int kw = 0; kw < kW; ++kw) {
+          const int ih = ih0 + kh, iw = iw0 + kw;
+          const bool inside = ih >= 0 && ih < H && iw >= 0 && iw < W;
+          const float xv = inside ? xn[((size_t)c * H + ih) * W + iw] : 0.0f;
+          const float *wp = w + ((size_t)d0 * C + c) * taps + kh * kW + kw;
+#pragma unroll
+          for (int j = 0; j < CONV_DB; ++j) {
+            const int dj = d0 + j < D ? j : 0;  // clamp: the extra lanes of a ragged group are not stored
+            acc[j] = fmaf(xv, wp[(size_t)dj * C * taps], acc[j]);
+          }
+        }
+#pragma unroll
+    for (int j = 0; j < CONV_DB; ++j) {
+      const int d = d0 + j;
+      if (d < D) {
+        float r = acc[j];
+        if (scale) r = fmaf(scale[d], r, bias[d]);
+        out[((size_t)n * D + d) * OH * OW + opix] = r;
       }
-  if (scale) acc = fmaf(scale[d], acc, bias[d]);
-  out[o] = acc;
+    }
+  }
 }
 
+// One workgroup per (row m, group of FC_NB outputs).  x and w are staged through LDS in
+// K-chunks with coalesced loads; thread j < FC_NB then runs the sequential fma chain of
+// output n0 + j over the chunk, so the summation order over k is ascending as specified.
+constexpr int FC_NB = 16;
+constexpr int FC_KC = 256;
 __global__ __launch_bounds__(256) void fc_f32_kernel(const float *__restrict__ x, const float *__restrict__ w,
                                                      const float *__restrict__ bias, int64_t M, int64_t K, int64_t N,
-                                                     int sign_input, float *__restrict__ out) {
-  const int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (o >= M * N) return;
-  const int64_t m = o / N, n = o - m * N;
-  const float *xr = x + m * K, *wr = w + n * K;
+                                                     int sign_input, float *__restrict__ out, int n_groups) {
+  __shared__ float sx[FC_KC];
+  __shared__ float sw[FC_NB][FC_KC + 1];
+  const int64_t m = blockIdx.x / n_groups;
+  const int64_t n0 = (int64_t)(blockIdx.x % n_groups) * FC_NB;
+  const int tid = threadIdx.x;
   float acc = 0.0f;
-  for (int64_t k = 0; k < K; ++k) {
-    float xv = xr[k];
-    if (sign_input) xv = xv >= 0.0f ? 1.0f : -1.0f;
-    acc = fmaf(xv, wr[k], acc);
+  for (int64_t k0 = 0; k0 < K; k0 += FC_KC) {
+    const int kc = (int)((K - k0) < FC_KC ? (K - k0) : FC_KC);
+    if (tid < kc) {
+      float xv = x[m * K + k0 + tid];
+      if (sign_input) xv = xv >= 0.0f ? 1.0f : -1.0f;
+      sx[tid] = xv;
+    }
+    for (int idx = tid; idx < FC_NB * FC_KC; idx += 256) {
+      const int j = idx / FC_KC, kk = idx % FC_KC;
+      if (n0 + j < N && kk < kc) sw[j][kk] = w[(n0 + j) * K + k0 + kk];
+    }
+    __syncthreads();
+    if (tid < FC_NB && n0 + tid < N) {
+      for (int kk = 0; kk < kc; ++kk) acc = fmaf(sx[kk], sw[tid][kk], acc);
+    }
+    __syncthreads();
   }
-  if (bias) acc = acc + bias[n];
-  out[o] = acc;
+  if (tid < FC_NB && n0 + tid < N) {
+    if (bias) acc = acc + bias[n0 + tid];
+    out[m * N + n0 + tid] = acc;
+  }
 }
 
-// 64 independent xor + popcount-accumulate pairs per round; the xor operand changes every
-// round so nothing can be hoisted.
+// 64 independent xor + popcount-accumulate pairs per round and nothing else in the loop
+// body but eight cheap updates of the xor operands (so nothing can be hoisted).
 __global__ __launch_bounds__(256) void valu_probe_kernel(int32_t *__restrict__ sink, int iters) {
   const uint32_t tid = blockIdx.x * 256u + threadIdx.x;
-  uint32_t b[8];
+  uint32_t a[8], b[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) b[j] = tid * 2654435761u + j * 40503u;
+  for (int j = 0; j < 8; ++j) {
+    b[j] = tid * 2654435761u + j * 40503u;
+    a[j] = 0x9e3779b9u * (j + 1) ^ tid;
+  }
   int acc[64];
 #pragma unroll
   for (int i = 0; i < 64; ++i) acc[i] = 0;
-  uint32_t a = 0x9e3779b9u ^ tid;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int i = 0; i < 64; ++i) acc[i] = __builtin_popcount((a + i) ^ b[i & 7]) + acc[i];
-    a = a * 1664525u + 1013904223u;
+    for (int i = 0; i < 64; ++i) {
+      const uint32_t x = a[i >> 3] ^ b[i & 7];
+      asm volatile("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc[i]) : "v"(x));
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) a[j] += b[j];
   }
   int tot = 0;
 #pragma unroll
@@ -137,14 +185,14 @@ extern "C" bnn_status bnn_conv2d_f32(const float *x, const float *w, int N, int 
   if ((scale == nullptr) != (bias == nullptr)) return BNN_ERR_NULL;
   if (!aligned16(x) || !aligned16(w) || !aligned16(out)) return BNN_ERR_ALIGN;
   const int64_t OH = bnn_conv_out_dim(H, kH, sH, pH), OW = bnn_conv_out_dim(W, kW, sW, pW);
-  const int64_t total = (int64_t)N * D * OH * OW;
+  const int64_t total = (int64_t)N * OH * OW;
   if (total > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
   {
     ProfScope ps(KID_CONV_F32, s);
     hipLaunchKernelGGL(conv2d_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, x, w, C, H, W, D, kH,
                        kW, sH, sW, pH, pW, (int)OH, (int)OW, scale, bias, out, FastDiv((uint32_t)OW),
-                       FastDiv((uint32_t)OH), FastDiv((uint32_t)D), (uint32_t)total);
+                       FastDiv((uint32_t)OH), (uint32_t)total);
   }
   return launch_status();
 }
@@ -155,12 +203,13 @@ extern "C" bnn_status bnn_fc_f32(const float *x, const float *w, const float *bi
   if (M == 0 || N == 0) return BNN_OK;
   if (!x || !w || !out) return BNN_ERR_NULL;
   if (!aligned16(x) || !aligned16(w) || !aligned16(out)) return BNN_ERR_ALIGN;
-  if (M * N > 0x7fffffffLL * 128) return BNN_ERR_UNSUPPORTED;
+  const int64_t n_groups = (N + FC_NB - 1) / FC_NB;
+  if (M * n_groups > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
   {
     ProfScope ps(KID_FC_F32, s);
-    hipLaunchKernelGGL(fc_f32_kernel, dim3((unsigned)((M * N + 255) / 256)), dim3(256), 0, s, x, w, bias, M, K, N,
-                       sign_input, out);
+    hipLaunchKernelGGL(fc_f32_kernel, dim3((unsigned)(M * n_groups)), dim3(256), 0, s, x, w, bias, M, K, N, sign_input,
+                       out, (int)n_groups);
   }
   return launch_status();
 }
