@@ -26,8 +26,8 @@ HBM_PEAK_GBS = 8000.0
 VALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12  # 39.32
 BOPS_PER_LANEOP = 32.0  # 2 lane-instructions (xor, popcount-accumulate) per 32 bit-MACs = 64 binary ops
 
-# HBM bytes per GEMM launch from rocprofv3 counters (profiles/); None until measured.
-GEMM_TRAFFIC_BYTES = None
+# HBM bytes per GEMM launch from rocprofv3 counters (profiles/), valid for the default workload only.
+GEMM_TRAFFIC_BYTES = 73.2e6  # cfg-4 stack: 439 MB per step over 6 GEMM launches (profiles/xnor_gemm_cfg4_vgg_stack_b256.md)
 
 
 def parse_args():
@@ -273,7 +273,8 @@ def main():
     achieved = lane_ops / gemm_s / 1e12
     roofline = {
         "kernel": "xnor_gemm", "bound": "alu", "achieved": round(achieved, 3), "peak": round(VALU_PEAK_TLANEOPS, 2),
-        "unit": "Tlaneop/s", "frac": round(achieved / VALU_PEAK_TLANEOPS, 4), "traffic": GEMM_TRAFFIC_BYTES,
+        "unit": "Tlaneop/s", "frac": round(achieved / VALU_PEAK_TLANEOPS, 4),
+        "traffic": GEMM_TRAFFIC_BYTES if args.workload == "cfg4" and args.reading == "A" else None,
         "launches_per_step": gemm_launches, "avg_launch_ms": round(gemm_s / max(gemm_launches, 1) * 1e3, 4),
         "gemm_only_TBOPS": round(wl["bops"] / gemm_s / 1e12, 2),
         "note": "achieved = 2*M*N*ceil(K/32) lane-ops summed over the step's GEMM launches / their summed HIP-event time",
