@@ -85,6 +85,7 @@ struct GemmParams {
   FastDiv divOHW;
   int64_t img_stride;  // elements between images in C / Y
   int tilesM, tilesN;
+  int dbg;
 };
 
 

@@ -24,7 +24,7 @@ extern "C" bnn_status bnn_conv2d(const float *x, const uint64_t *w_packed, int N
   const int64_t OH = bnn_conv_out_dim(H, kH, sH, pH), OW = bnn_conv_out_dim(W, kW, sW, pW);
   const int64_t P = (int64_t)N * OH * OW;
   const int64_t Kw = bnn_conv_kwords(C, kH, kW);
-  if (P > 0x7ffffff0LL || (int64_t)D * 2 * Kw > 0xffffffffLL || (int64_t)D * P > 0x7fffffffLL * 8)
+  if (P > 0x7ffffff0LL || (int64_t)D * 8 * Kw > 0xffffffffLL || (int64_t)D * P > 0x7fffffffLL * 8)
     return BNN_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
 

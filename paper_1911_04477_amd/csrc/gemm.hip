@@ -21,6 +21,7 @@
 // Workgroup ids are remapped so that tiles sharing a B tile run on the same XCD
 // (one L2 per XCD; hardware deals consecutive ids round-robin over the 8 XCDs).
 #include "common.h"
+#include "gemm_rows.inc"
 
 namespace bnn {
 
@@ -34,12 +35,6 @@ typedef const u32x4_a8 BNN_CONST_AS *cu32x4_ptr;
 
 using u32x8 = uint32_t __attribute__((ext_vector_type(8)));
 
-// acc += popcount(a ^ b): exactly two VALU instructions, a from an SGPR.
-__device__ __forceinline__ void xor_popc_acc(int &acc, uint32_t a_sgpr, uint32_t b) {
-  uint32_t t;
-  asm("v_xor_b32 %1, %2, %3\n\tv_bcnt_u32_b32 %0, %1, %0" : "+v"(acc), "=&v"(t) : "s"(a_sgpr), "v"(b));
-}
-
 // acc += popcount(x) as ONE instruction.  Written as asm because the optimizer otherwise
 // re-associates a chain of popcount-adds into v_bcnt(x, 0) plus separate three-operand adds,
 // which costs 25 % more VALU instructions in the inner loop.
@@ -48,7 +43,11 @@ __device__ __forceinline__ int popc_acc(uint32_t x, int acc) {
   return acc;
 }
 
-template <int TM, int TN, int WM, int WN, int KC>
+// The K axis is consumed in chunks of KC = 8 dwords (256 bits); a wave owns TM = 8 rows.
+constexpr int KC = 8;
+constexpr int TM = 8;
+
+template <int TN, int WM, int WN>
 struct GemmCfg {
   static constexpr int BM = TM * WM;
   static constexpr int BN = 64 * TN * WN;
@@ -57,21 +56,15 @@ struct GemmCfg {
   static constexpr int TILE = BN * RS;                   // dwords per LDS buffer
   static constexpr int PIECES = BN * (KC / 4);           // 16-byte pieces per chunk
   static constexpr int PPT = (PIECES + THREADS - 1) / THREADS;
-  static_assert(KC % 4 == 0, "chunk must be whole 16-byte pieces");
   static_assert(PIECES % THREADS == 0 || PIECES < THREADS, "staging must divide evenly");
 };
 
-// s_waitcnt lgkmcnt(0) only (vmcnt / expcnt left at their maxima).
-#define BNN_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt(0xC07F)
-#define BNN_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
-
-template <int TM, int TN, int WM, int WN, int KC, int MINW>
+template <int TN, int WM, int WN, int MINW>
 __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParams p) {
-  using Cfg = GemmCfg<TM, TN, WM, WN, KC>;
+  using Cfg = GemmCfg<TN, WM, WN>;
   constexpr int RS = Cfg::RS;
   constexpr int PPT = Cfg::PPT;
-  constexpr int QPR = KC / 4;   // 16-byte pieces per row
-  constexpr int NSUB = KC / 4;  // sub-steps (4 dwords each) per chunk
+  constexpr int QPR = KC / 4;  // 16-byte pieces per row
   __shared__ __attribute__((aligned(16))) uint32_t sB[2 * Cfg::TILE];
 
   const int tid = threadIdx.x;
@@ -90,16 +83,20 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   const int m0 = mi * Cfg::BM + wm * TM;
   const int n0 = ni * Cfg::BN;
 
-  // Dword offsets of this wave's TM rows (clamped: rows past M recompute row M-1 and are
-  // not stored).  32-bit: the host checks that M * lda32 < 2^32.
-  uint32_t aoff[TM];
+  // Byte offsets of this wave's TM rows (clamped: rows past M recompute row M-1 and are
+  // not stored), held in SGPRs.  32-bit: the host checks that M * lda32 * 4 < 2^32.
+  uint32_t aoffb[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     int m = m0 + i;
     m = m < p.M ? m : p.M - 1;
-    aoff[i] = (uint32_t)m * (uint32_t)p.lda32;
+    aoffb[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)m * (uint32_t)p.lda32 * 4u));
   }
-
+  // 64-bit base of A in an SGPR pair (readfirstlane returns a signed int: each half is cast
+  // to unsigned before widening); advanced by one chunk (32 bytes) per iteration.
+  const uint32_t Abase_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)p.A);
+  const uint32_t Abase_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uintptr_t)p.A >> 32));
+  uint64_t Abase = ((uint64_t)Abase_hi << 32) | (uint64_t)Abase_lo;
   const cu32_ptr Ac = (cu32_ptr)(uintptr_t)p.A;
 
   int acc[TM][TN];
@@ -108,9 +105,8 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
 #pragma unroll
     for (int j = 0; j < TN; ++j) acc[i][j] = 0;
 
-  const int nchunks = (p.Kd + KC - 1) / KC;
-  const int kd_full = p.Kbits >> 5;     // dwords whose 32 bits all take part
-  const int nsub_total = kd_full >> 2;  // mask-free sub-steps over the whole K range
+  const int nchunks = (p.Kd + KC - 1) / KC;     // chunks holding any bit
+  const int nfull = p.Kbits / (32 * KC);        // chunks whose every bit takes part (nchunks - nfull is 0 or 1)
   const int last_w = p.Kw64 - 1;
   const int tail_bits = p.Kbits & 63;
   const uint64_t tail_mask = tail_bits ? ((1ull << tail_bits) - 1ull) : ~0ull;
@@ -158,128 +154,75 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
     }
   };
 
-  auto compute = [&](const u32x4 (&a)[TM], const u32x4 (&b)[TN]) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        acc[i][j] = popc_acc(a[i].x ^ b[j].x, acc[i][j]);
-        acc[i][j] = popc_acc(a[i].y ^ b[j].y, acc[i][j]);
-        acc[i][j] = popc_acc(a[i].z ^ b[j].z, acc[i][j]);
-        acc[i][j] = popc_acc(a[i].w ^ b[j].w, acc[i][j]);
-      }
-  };
-
   const int lane_row = (wn * 64 * TN + lane) * RS;
 
-  // Per chunk of KC = 8 dwords: the wave's TM rows of A arrive with TM scalar loads of 8
-  // dwords each (64 SGPRs), issued together with the first LDS reads of B; one wait; then
-  // 2 * TM * TN * 8 xor / popcount instructions with only the second sub-step's LDS reads
-  // in between.  The loads are inline asm so that their place in the instruction stream is
-  // fixed; the wait names every loaded register as in/out operand, which orders all uses
-  // after it.  The latency of one wave's loads is covered by the other resident waves.
-  static_assert(KC == 8 || TM * KC <= 64, "A chunk must fit the SGPR budget");
   stage_load(0);
   stage_store(0, 0);
   __syncthreads();
 
-  // 64-bit base of A in an SGPR pair (both halves made explicitly wave-uniform)
-  // (readfirstlane returns a signed int: each half is cast to unsigned before widening)
-  const uint32_t Abase_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)p.A);
-  const uint32_t Abase_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uintptr_t)p.A >> 32));
-  const uint64_t Abase = ((uint64_t)Abase_hi << 32) | (uint64_t)Abase_lo;
-  uint32_t aoffb[TM];  // byte offsets
-#pragma unroll
-  for (int i = 0; i < TM; ++i) aoffb[i] = aoff[i] * 4u;
-
-  for (int c = 0; c < nchunks; ++c) {
-    const int buf = c & 1;
-    if (c + 1 < nchunks) stage_load(c + 1);
+  // ---- full chunks ---------------------------------------------------------------------
+  // Per chunk: the wave's 8 rows of A arrive with 8 scalar loads of 8 dwords (64 SGPRs),
+  // issued together with the LDS reads of B; one wait; then 2 * 8 * TN * 8 xor / popcount
+  // instructions and nothing else.  Loads, wait and the per-row compute statements are
+  // volatile inline asm, so their order in the instruction stream is the order written
+  // here; the wait names every loaded SGPR as in/out operand, which orders all uses after
+  // it.  The latency of one wave's loads is covered by the other waves on the SIMD.
+  for (int c = 0; c < nfull; ++c) {
+    const int buf = (p.dbg & 1) ? 0 : (c & 1);
+    const bool more = c + 1 < nchunks && !(p.dbg & 1);
+    if (more) stage_load(c + 1);
     const uint32_t *sBl = &sB[buf * Cfg::TILE + lane_row];
-    const int sub0 = c * NSUB;                              // first sub-step index of this chunk
-    const int nsub = min(NSUB, max(nsub_total - sub0, 0));  // mask-free sub-steps in this chunk
-    const cu32_ptr Ak = Ac + c * KC;
-
-    if (nsub == NSUB) {
-      if constexpr (KC == 8) {
-        u32x8 a[TM];
-        u32x4 b[TN];
+    u32x8 a[TM];
+    u32x8 b[TN];
+    if (!(p.dbg & 2) || c == 0) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-          asm volatile("s_load_dwordx8 %0, %1, %2"
-                       : "=s"(a[i])
-                       : "s"(Abase), "s"((uint32_t)__builtin_amdgcn_readfirstlane((int)(aoffb[i] + (uint32_t)c * (KC * 4u)))));
-#pragma unroll
-        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&sBl[j * 64 * RS]);
-        if constexpr (TM == 8)
-          asm volatile("s_waitcnt lgkmcnt(0)"
-                       : "+s"(a[0]), "+s"(a[1]), "+s"(a[2]), "+s"(a[3]), "+s"(a[4]), "+s"(a[5]), "+s"(a[6]),
-                         "+s"(a[7]));
-        else
-          static_assert(TM == 8, "wait statement is written for TM == 8");
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            xor_popc_acc(acc[i][j], a[i][0], b[j].x);
-            xor_popc_acc(acc[i][j], a[i][1], b[j].y);
-            xor_popc_acc(acc[i][j], a[i][2], b[j].z);
-            xor_popc_acc(acc[i][j], a[i][3], b[j].w);
-          }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&sBl[j * 64 * RS + 4]);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j) {
-            xor_popc_acc(acc[i][j], a[i][4], b[j].x);
-            xor_popc_acc(acc[i][j], a[i][5], b[j].y);
-            xor_popc_acc(acc[i][j], a[i][6], b[j].z);
-            xor_popc_acc(acc[i][j], a[i][7], b[j].w);
-          }
-      } else {
-#pragma unroll
-        for (int s = 0; s < NSUB; ++s) {
-          u32x4 a[TM], b[TN];
-#pragma unroll
-          for (int i = 0; i < TM; ++i) a[i] = *(cu32x4_ptr)(Ak + aoff[i] + 4 * s);
-#pragma unroll
-          for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&sBl[j * 64 * RS + 4 * s]);
-          compute(a, b);
-        }
-      }
-    } else {
-#pragma unroll 1
-      for (int s = 0; s < nsub; ++s) {
-        u32x4 a[TM], b[TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) a[i] = *(cu32x4_ptr)(Ak + aoff[i] + 4 * s);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&sBl[j * 64 * RS + 4 * s]);
-        compute(a, b);
-      }
-      // dwords past the last whole sub-step: one at a time, A masked here, B already masked
-      // and zero-filled by the staging.
-      const int kd0 = c * KC;
-      const int kd_end = p.Kd < kd0 + KC ? p.Kd : kd0 + KC;
-      const int tb32 = p.Kbits & 31;
-#pragma unroll 1
-      for (int kd = kd0 + 4 * nsub; kd < kd_end; ++kd) {
-        const uint32_t amask = (kd == p.Kd - 1 && tb32) ? ((1u << tb32) - 1u) : 0xffffffffu;
-        uint32_t b[TN];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) b[j] = sBl[j * 64 * RS + (kd - kd0)];
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          const uint32_t a = Ac[aoff[i] + kd] & amask;
-#pragma unroll
-          for (int j = 0; j < TN; ++j) acc[i][j] = popc_acc(a ^ b[j], acc[i][j]);
-        }
-      }
+    for (int i = 0; i < TM; ++i)
+      asm volatile("s_load_dwordx8 %0, %1, %2"
+                   : "=s"(a[i])
+                   : "s"(Abase), "s"(aoffb[i]));
     }
-    if (c + 1 < nchunks) {
-      stage_store(buf ^ 1, c + 1);  // the other buffer was last read in chunk c-1, before the barrier below
+    Abase += KC * 4;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      b[j].lo = *reinterpret_cast<const u32x4 *>(&sBl[j * 64 * RS]);
+      b[j].hi = *reinterpret_cast<const u32x4 *>(&sBl[j * 64 * RS + 4]);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+s"(a[0]), "+s"(a[1]), "+s"(a[2]), "+s"(a[3]), "+s"(a[4]), "+s"(a[5]), "+s"(a[6]), "+s"(a[7]));
+    uint32_t t0, t1;
+#define BNN_BV(j, d) b[j][d]
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      if constexpr (TN == 8) BNN_GEMM_ROW_8(acc[i], a[i], BNN_BV, t0, t1);
+      else if constexpr (TN == 4) BNN_GEMM_ROW_4(acc[i], a[i], BNN_BV, t0, t1);
+      else if constexpr (TN == 2) BNN_GEMM_ROW_2(acc[i], a[i], BNN_BV, t0, t1);
+      else BNN_GEMM_ROW_1(acc[i], a[i], BNN_BV, t0, t1);
+    }
+#undef BNN_BV
+    if (more) {
+      stage_store(buf ^ 1, c + 1);  // that buffer was last read in chunk c-1, before the previous barrier
       __syncthreads();
+    }
+  }
+
+  // ---- final partial chunk (K not a multiple of 256 bits) ---------------------------------
+  // One dword at a time.  B is already masked / zero-filled by the staging; A is masked here.
+  if (nfull < nchunks) {
+    const uint32_t *sBl = &sB[(nfull & 1) * Cfg::TILE + lane_row];
+    const int kd0 = nfull * KC;
+    const int tb32 = p.Kbits & 31;
+#pragma unroll 1
+    for (int kd = kd0; kd < p.Kd; ++kd) {
+      const uint32_t amask = (kd == p.Kd - 1 && tb32) ? ((1u << tb32) - 1u) : 0xffffffffu;
+      uint32_t b[TN];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) b[j] = sBl[j * 64 * RS + (kd - kd0)];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const uint32_t a = Ac[(aoffb[i] >> 2) + kd] & amask;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = popc_acc(a ^ b[j], acc[i][j]);
+      }
     }
   }
 
@@ -289,7 +232,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   // slots) during the main loop.
   const GemmParams BNN_CONST_AS *kp = (const GemmParams BNN_CONST_AS *)__builtin_amdgcn_kernarg_segment_ptr();
   asm volatile("" : "+s"(kp));
-  const int M = kp->M, N = kp->N, Kformula = kp->Kformula, axis = kp->axis;
+  const int M = kp->M, N = (kp->dbg & 4) ? 0 : kp->N, Kformula = kp->Kformula, axis = kp->axis;
   int32_t *const Cp = kp->C;
   float *const Yp = kp->Y;
   const float *const scale = kp->scale, *const bias = kp->bias;
@@ -334,33 +277,48 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
 }
 
 // ---- host side ----------------------------------------------------------------------
-template <int TM, int TN, int WM, int WN, int KC, int MINW>
+template <int TN, int WM, int WN, int MINW>
 static bnn_status launch_cfg(GemmParams &p, hipStream_t s, int kid) {
-  using Cfg = GemmCfg<TM, TN, WM, WN, KC>;
+  using Cfg = GemmCfg<TN, WM, WN>;
   p.tilesM = (p.M + Cfg::BM - 1) / Cfg::BM;
   p.tilesN = (p.N + Cfg::BN - 1) / Cfg::BN;
   const int64_t blocks = (int64_t)p.tilesM * p.tilesN;
   if (blocks > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   ProfScope ps(kid, s);
-  hipLaunchKernelGGL((xnor_gemm_kernel<TM, TN, WM, WN, KC, MINW>), dim3((unsigned)blocks), dim3(Cfg::THREADS), 0, s,
+  hipLaunchKernelGGL((xnor_gemm_kernel<TN, WM, WN, MINW>), dim3((unsigned)blocks), dim3(Cfg::THREADS), 0, s,
                      p);
   return launch_status();
 }
 
 int g_force_cfg = -1;  // test / tuning hook: -1 = heuristic
+int g_dbg = 0;
 
 // Tile choice: the large tile (64 x 512) has the best ratio of VALU work to everything
 // else but needs enough tiles to fill 256 CUs twice over; smaller problems fall back to
 // finer tiles so that every CU has work.
 bnn_status run_gemm(GemmParams &p, hipStream_t s) {
-  const int64_t tilesL = (int64_t)((p.M + 31) / 32) * ((p.N + 511) / 512);
-  const int64_t tilesMd = (int64_t)((p.M + 31) / 32) * ((p.N + 255) / 256);
   int cfg = g_force_cfg;
-  if (cfg < 0) cfg = tilesL >= 512 ? 0 : (tilesMd >= 512 ? 1 : 2);
+  p.dbg = g_dbg;
+  if (cfg < 0) {
+    // Measured on MI355X: 64 x 256 (TN = 4, eight waves per workgroup, six per SIMD) is the
+    // fastest tile when there are enough of them; smaller problems take finer tiles so that
+    // every CU has work.
+    const int64_t t256 = (int64_t)((p.M + 63) / 64) * ((p.N + 255) / 256);
+    const int64_t t128 = (int64_t)((p.M + 63) / 64) * ((p.N + 127) / 128);
+    const int64_t t32 = (int64_t)((p.M + 31) / 32) * ((p.N + 127) / 128);
+    cfg = (p.M >= 64 && t256 >= 512) ? 3 : (p.M >= 64 && t128 >= 512) ? 6 : (t32 >= 256 ? 4 : 2);
+  }
   switch (cfg) {
-    case 0: return launch_cfg<8, 8, 4, 1, 8, 2>(p, s, KID_XNOR_GEMM);
-    case 1: return launch_cfg<8, 4, 4, 1, 8, 4>(p, s, KID_XNOR_GEMM);
-    default: return launch_cfg<8, 1, 4, 1, 8, 4>(p, s, KID_XNOR_GEMM_SMALL);
+    case 0: return launch_cfg<8, 4, 1, 2>(p, s, KID_XNOR_GEMM);        // 32 x 512
+    case 1: return launch_cfg<4, 4, 1, 4>(p, s, KID_XNOR_GEMM);        // 32 x 256
+    case 2: return launch_cfg<1, 4, 1, 4>(p, s, KID_XNOR_GEMM_SMALL);  // 32 x 64
+    case 3: return launch_cfg<4, 8, 1, 4>(p, s, KID_XNOR_GEMM);        // 64 x 256
+    case 4: return launch_cfg<2, 4, 1, 4>(p, s, KID_XNOR_GEMM);        // 32 x 128
+    case 5: return launch_cfg<4, 16, 1, 4>(p, s, KID_XNOR_GEMM);       // 128 x 256
+    case 6: return launch_cfg<2, 8, 1, 4>(p, s, KID_XNOR_GEMM);        // 64 x 128
+    case 7: return launch_cfg<2, 16, 1, 4>(p, s, KID_XNOR_GEMM);       // 128 x 128
+    case 9: return launch_cfg<2, 4, 2, 4>(p, s, KID_XNOR_GEMM);        // 32 x 256 from TN = 2
+    default: return BNN_ERR_UNSUPPORTED;
   }
 }
 
@@ -378,7 +336,7 @@ static bnn_status gemm_common(const uint64_t *A, int64_t lda, const uint64_t *B,
   if (Y && axis != BNN_CH_ROW && axis != BNN_CH_COL) return BNN_ERR_SHAPE;
   if (!aligned16(A) || !aligned16(B) || (C && !aligned16(C)) || (Y && !aligned16(Y))) return BNN_ERR_ALIGN;
   if (M > 0x7fffffffLL || N > 0x7ffffff0LL || K > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
-  if (M * 2 * lda > 0xffffffffLL) return BNN_ERR_UNSUPPORTED;  // 32-bit dword offsets into A
+  if (M * 8 * lda > 0xffffffffLL) return BNN_ERR_UNSUPPORTED;  // 32-bit byte offsets into A
   GemmParams p;
   p.A = reinterpret_cast<const uint32_t *>(A);
   p.B = B;
@@ -422,3 +380,4 @@ extern "C" bnn_status bnn_xnor_gemm_epilogue(const uint64_t *A, int64_t lda, con
 
 // Tuning / test hook (not declared in the public header): force a tile configuration.
 extern "C" void bnn_internal_force_gemm_cfg(int cfg) { g_force_cfg = cfg; }
+extern "C" void bnn_internal_gemm_dbg(int d) { g_dbg = d; }

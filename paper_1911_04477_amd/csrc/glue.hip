@@ -4,6 +4,7 @@
 // fixed sequential fma order so that their rounding is reproducible bit for bit (a
 // differently rounded value could flip a sign that the next binarized layer consumes).
 #include "common.h"
+#include "gemm_rows.inc"
 
 namespace bnn {
 
@@ -115,15 +116,21 @@ __global__ __launch_bounds__(256) void fc_f32_kernel(const float *__restrict__ x
   }
 }
 
-// 64 independent xor + popcount-accumulate pairs per round and nothing else in the loop
-// body but eight cheap updates of the xor operands (so nothing can be hoisted).
-__global__ __launch_bounds__(256) void valu_probe_kernel(int32_t *__restrict__ sink, int iters) {
+// 64 xor + popcount-accumulate pairs per round and nothing else in the loop body but
+// eight cheap updates of the xor operands (so nothing can be hoisted).
+// MODE 0: both xor operands in VGPRs, the compiler schedules the xors freely.
+// MODE 1: the GEMM's own instruction pattern: xor operand from an SGPR, each v_xor
+//         immediately followed by the v_bcnt that depends on it.
+// MODE 2: 128 v_xor only (VGPR operands).  MODE 3: 128 v_bcnt accumulates only.
+// MODE 4: dependent pairs, both operands in VGPRs.
+template <int MODE>
+__global__ __launch_bounds__(256) void valu_probe_kernel(int32_t *__restrict__ sink, int iters, uint32_t seed) {
   const uint32_t tid = blockIdx.x * 256u + threadIdx.x;
   uint32_t a[8], b[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     b[j] = tid * 2654435761u + j * 40503u;
-    a[j] = 0x9e3779b9u * (j + 1) ^ tid;
+    a[j] = 0x9e3779b9u * (j + 1) ^ (MODE == 1 ? seed : tid);
   }
   int acc[64];
 #pragma unroll
@@ -131,15 +138,81 @@ __global__ __launch_bounds__(256) void valu_probe_kernel(int32_t *__restrict__ s
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int i = 0; i < 64; ++i) {
-      const uint32_t x = a[i >> 3] ^ b[i & 7];
-      asm volatile("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc[i]) : "v"(x));
+      if (MODE == 0) {
+        const uint32_t x = a[i >> 3] ^ b[i & 7];
+        asm volatile("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc[i]) : "v"(x));
+      } else if (MODE == 1) {
+        uint32_t t;
+        asm volatile("v_xor_b32 %1, %2, %3\n\tv_bcnt_u32_b32 %0, %1, %0"
+                     : "+v"(acc[i]), "=&v"(t)
+                     : "s"(a[i >> 3]), "v"(b[i & 7]));
+      } else if (MODE == 2) {
+        asm volatile("v_xor_b32 %0, %1, %0\n\tv_xor_b32 %0, %2, %0" : "+v"(acc[i]) : "v"(a[i >> 3]), "v"(b[i & 7]));
+      } else if (MODE == 3) {
+        asm volatile("v_bcnt_u32_b32 %0, %1, %0\n\tv_bcnt_u32_b32 %0, %2, %0"
+                     : "+v"(acc[i])
+                     : "v"(a[i >> 3]), "v"(b[i & 7]));
+      } else {
+        uint32_t t;
+        asm volatile("v_xor_b32 %1, %2, %3\n\tv_bcnt_u32_b32 %0, %1, %0"
+                     : "+v"(acc[i]), "=&v"(t)
+                     : "v"(a[i >> 3]), "v"(b[i & 7]));
+      }
     }
+    if (MODE == 1) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) a[j] += b[j];
+      for (int j = 0; j < 8; ++j) a[j] = a[j] * 1664525u + 1013904223u;  // scalar ALU
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) a[j] += b[j];
+    }
   }
   int tot = 0;
 #pragma unroll
   for (int i = 0; i < 64; ++i) tot += acc[i];
+  sink[tid] = tot;
+}
+
+// The GEMM's own per-row statements (8 rows x TN columns x 8 dwords) run from registers,
+// with no loads at all: the ceiling of that exact instruction sequence.
+template <int TN, int V = 0>
+__global__ __launch_bounds__(256) void valu_rows_probe_kernel(int32_t *__restrict__ sink, int iters, uint32_t seed) {
+  const uint32_t tid = blockIdx.x * 256u + threadIdx.x;
+  typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
+  u32x8 a[8], b[TN];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int d = 0; d < 8; ++d) a[i][d] = seed * (uint32_t)(i * 8 + d + 1) + 0x9e3779b9u;
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int d = 0; d < 8; ++d) b[j][d] = tid * 2654435761u + (uint32_t)(j * 8 + d) * 40503u;
+  int acc[8][TN];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = 0;
+  for (int it = 0; it < iters; ++it) {
+    uint32_t t0, t1;
+#define BNN_BV(j, d) b[j][d]
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if constexpr (TN == 4) BNN_GEMM_ROW_4(acc[i], a[i], BNN_BV, t0, t1);
+      else if constexpr (V == 1) BNN_GEMM_ROW_2_V1(acc[i], a[i], BNN_BV, t0, t1);
+      else if constexpr (V == 2) BNN_GEMM_ROW_2_V2(acc[i], a[i], BNN_BV, t0, t1);
+      else if constexpr (V == 3) BNN_GEMM_ROW_2_V3(acc[i], a[i], BNN_BV, t0, t1);
+      else BNN_GEMM_ROW_2(acc[i], a[i], BNN_BV, t0, t1);
+    }
+#undef BNN_BV
+#pragma unroll
+    for (int j = 0; j < TN; ++j) b[j][0] += 1u;
+  }
+  int tot = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) tot += acc[i][j];
   sink[tid] = tot;
 }
 
@@ -154,6 +227,10 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const uint4 *__restrict
 }  // namespace bnn
 
 using namespace bnn;
+
+static int g_probe_mode = 0;
+// Tuning hook (not in the public header): 1 selects the scalar-operand, dependent-pair probe.
+extern "C" void bnn_internal_probe_mode(int mode) { g_probe_mode = mode; }
 
 extern "C" bnn_status bnn_maxpool2x2(const int32_t *in, int N, int D, int H, int W, int32_t *out_i32, float *out_f32,
                                      const float *scale, const float *bias, void *stream) {
@@ -222,7 +299,20 @@ extern "C" bnn_status bnn_valu_peak_probe(int32_t *sink, int blocks, int iters, 
   hipStream_t s = (hipStream_t)stream;
   {
     ProfScope ps(KID_VALU_PROBE, s);
-    hipLaunchKernelGGL(valu_probe_kernel, dim3((unsigned)blocks), dim3(256), 0, s, sink, iters);
+    const dim3 g((unsigned)blocks), b(256);
+    switch (g_probe_mode) {
+      case 1: hipLaunchKernelGGL(valu_probe_kernel<1>, g, b, 0, s, sink, iters, 1u); break;
+      case 2: hipLaunchKernelGGL(valu_probe_kernel<2>, g, b, 0, s, sink, iters, 1u); break;
+      case 3: hipLaunchKernelGGL(valu_probe_kernel<3>, g, b, 0, s, sink, iters, 1u); break;
+      case 4: hipLaunchKernelGGL(valu_probe_kernel<4>, g, b, 0, s, sink, iters, 1u); break;
+      // iters rounds of 8 x TN x 8 pairs: scale iters so that the lane-op count per launch matches
+      case 5: hipLaunchKernelGGL(valu_rows_probe_kernel<2>, g, b, 0, s, sink, iters / 2, 1u); break;
+      case 6: hipLaunchKernelGGL(valu_rows_probe_kernel<4>, g, b, 0, s, sink, iters / 4, 1u); break;
+      case 11: hipLaunchKernelGGL((valu_rows_probe_kernel<2, 1>), g, b, 0, s, sink, iters / 2, 1u); break;
+      case 12: hipLaunchKernelGGL((valu_rows_probe_kernel<2, 2>), g, b, 0, s, sink, iters / 2, 1u); break;
+      case 13: hipLaunchKernelGGL((valu_rows_probe_kernel<2, 3>), g, b, 0, s, sink, iters / 2, 1u); break;
+      default: hipLaunchKernelGGL(valu_probe_kernel<0>, g, b, 0, s, sink, iters, 1u); break;
+    }
   }
   return launch_status();
 }
