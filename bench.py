@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg4", choices=["cfg4", "cfg2", "cfg3", "cfg5a", "cfg5b"])
     ap.add_argument("--reading", default="A", choices=["A", "B"])
+    ap.add_argument("--stack", default="fused", choices=["fused", "unfused"],
+                    help="cfg4 only: activations packed between layers (fused) or fp32/int32 NCHW maps (unfused)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-kernel side measurements")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
@@ -96,10 +98,10 @@ def build_workload(name, args):
         return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
 
     if name == "cfg4":
-        from paper_1911_04477_amd.stack import VggStack
+        from paper_1911_04477_amd.stack import VggStack, VggStackFused
         batch = 256
         d = inputs.cfg4(batch=batch, reading=args.reading)
-        net = VggStack(d["layers"], d["params"], batch=batch, device=dev)
+        net = (VggStackFused if args.stack == "fused" else VggStack)(d["layers"], d["params"], batch=batch, device=dev)
         x = up(d["x"])
         shapes = []
         for L in d["layers"]:
@@ -121,8 +123,9 @@ def build_workload(name, args):
             return 2.0 * inputs.stack_bit_macs(d["layers"], n), dt, f"{n} of {batch} images through the whole stack"
 
         return dict(fn=lambda: net.forward(x), bops=2.0 * bit_macs, gemm_shapes=shapes,
-                    label=f"cfg4_vgg_small_stack_b{batch}_reading{args.reading}", oracle=oracle_sample,
-                    extra={"batch": batch, "reading": args.reading})
+                    label=f"cfg4_vgg_small_stack_b{batch}_reading{args.reading}_{args.stack}", oracle=oracle_sample,
+                    extra={"batch": batch, "reading": args.reading, "activations": "packed 1-bit NHWC between layers"
+                           if args.stack == "fused" else "fp32 / int32 NCHW maps between layers"})
 
     if name == "cfg2":
         d = inputs.cfg2()
@@ -274,7 +277,7 @@ def main():
     roofline = {
         "kernel": "xnor_gemm", "bound": "alu", "achieved": round(achieved, 3), "peak": round(VALU_PEAK_TLANEOPS, 2),
         "unit": "Tlaneop/s", "frac": round(achieved / VALU_PEAK_TLANEOPS, 4),
-        "traffic": GEMM_TRAFFIC_BYTES if args.workload == "cfg4" and args.reading == "A" else None,
+        "traffic": GEMM_TRAFFIC_BYTES if args.workload == "cfg4" and args.reading == "A" and args.stack == "fused" else None,
         "launches_per_step": gemm_launches, "avg_launch_ms": round(gemm_s / max(gemm_launches, 1) * 1e3, 4),
         "gemm_only_TBOPS": round(wl["bops"] / gemm_s / 1e12, 2),
         "note": "achieved = 2*M*N*ceil(K/32) lane-ops summed over the step's GEMM launches / their summed HIP-event time",

@@ -152,6 +152,49 @@ bnn_status bnn_conv2d(const float *x, const uint64_t *w_packed, int N, int C, in
 size_t bnn_conv2d_workspace_bytes(int N, int C, int H, int W, int kH, int kW, int sH, int sW, int pH,
                                   int pW);
 
+/*
+ * bnn_conv2d_packed -- the same forward graph with activations kept packed between
+ * layers (1 bit per activation in memory): the input is a packed NHWC image, and with the
+ * binarizing epilogue the output is the packed NHWC image the next layer consumes.
+ *   x_packed  [N, H, W, ceil(C/64)] uint64: pixel-major, channel c in bit (c mod 64) of word
+ *             (c div 64), pad bits 0 (what bnn_conv2d_f32_sign or this function writes)
+ *   w_packed  [D, bnn_conv_kwords(C,kH,kW)] from bnn_pack_conv_weight
+ *   Exactly one kind of output per call:
+ *     out_i32 and/or out_f32  [N, D, OH, OW] NCHW as in bnn_conv2d (pool must be 0), or
+ *     out_packed [N, OH', OW', ceil(D/64)] uint64 with
+ *         bit d = ( fma(scale[d], (float)a, bias[d]) >= 0 ),
+ *         a = acc[n,d,oh,ow] for pool == 0 (OH' = OH, OW' = OW), or the maximum of acc over
+ *         the 2x2 window for pool == 2 (OH' = OH/2, OW' = OW/2; OH and OW must be even):
+ *         conv -> max-pool on int32 -> affine -> sign, the block order of the stack.
+ *   scale, bias [D] are required for out_f32 and out_packed.  No workspace is needed: the
+ *   patch matrix is never materialised.
+ */
+bnn_status bnn_conv2d_packed(const uint64_t *x_packed, const uint64_t *w_packed, int N, int C, int H,
+                             int W, int D, int kH, int kW, int sH, int sW, int pH, int pW, int pool,
+                             int32_t *out_i32, float *out_f32, uint64_t *out_packed,
+                             const float *scale, const float *bias, void *stream);
+
+/*
+ * bnn_conv2d_f32_sign -- real-valued first layer of the stack with binarized output:
+ * bnn_conv2d_f32 (same fixed summation order) followed by fma(scale[d], acc, bias[d]) and
+ * the sign, written as a packed NHWC image [N, OH, OW, ceil(D/64)].  Limited to
+ * C*kH*kW <= 32 taps and D*(C*kH*kW rounded up to 4) + 2*D <= 16384 floats of filter data
+ * (BNN_ERR_UNSUPPORTED otherwise).
+ */
+bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N, int C, int H, int W, int D,
+                               int kH, int kW, int sH, int sW, int pH, int pW, const float *scale,
+                               const float *bias, uint64_t *out_packed, void *stream);
+
+/*
+ * bnn_pack_fc_weight_nhwc -- encode the weight of a fully-connected layer whose input is a
+ * flattened NCHW map [C, H, W] so that it can be multiplied with that map's packed NHWC
+ * form: w [Nout, C*H*W] fp32 -> w_packed [Nout, H*W*ceil(C/64)] uint64 with the reduction
+ * axis re-ordered to (h, w, c), each pixel padded to whole words.  (A permutation applied to
+ * the reduction axis of both operands does not change the product.)
+ */
+bnn_status bnn_pack_fc_weight_nhwc(const float *w, int64_t Nout, int C, int H, int W,
+                                   uint64_t *w_packed, void *stream);
+
 /* ---- glue kernels of the binarized VGG-small stack (not part of the paper's kernel,
  *      which covers convolution only -- section 4.4) -------------------------------- */
 

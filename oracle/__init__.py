@@ -233,6 +233,25 @@ def im2col_packed(x, kH, kW, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
     return cols.reshape(N * OH * OW, kH * kW * Cw)
 
 
+def pack_nhwc(y) -> np.ndarray:
+    """fp32 NCHW map -> packed NHWC image uint64 [N, H, W, ceil(C/64)]: bit c of a pixel is
+    1 iff y[n, c, h, w] >= 0 (the encoding of section 3.1 applied along the channel axis)."""
+    y = _f32(y)
+    N, C, H, W = y.shape
+    rows = np.transpose(y, (0, 2, 3, 1)).reshape(N * H * W, C)
+    return encode_rows(rows).reshape(N, H, W, packed_words(C))
+
+
+def pack_fc_weight_nhwc(w, C: int, H: int, W: int) -> np.ndarray:
+    """[Nout, C*H*W] fp32 (NCHW flatten order) -> uint64 [Nout, H*W*ceil(C/64)] with the
+    reduction axis re-ordered to (h, w, c) and every pixel padded to whole words."""
+    w = _f32(w)
+    n_out = w.shape[0]
+    assert w.shape[1] == C * H * W
+    rows = np.transpose(w.reshape(n_out, C, H * W), (0, 2, 1)).reshape(n_out * H * W, C)
+    return encode_rows(rows).reshape(n_out, H * W * packed_words(C))
+
+
 # ----------------------------------------------------------------------------
 # The VGG-small stack as a composition of the definitions above.
 # Block order: conv -> int32 -> (2x2 max-pool on int32 if pooled) -> fma(scale, acc,

@@ -33,6 +33,9 @@ SIGNATURES = {
     "bnn_xnor_gemm_epilogue": (_i32, [_p, _i64, _p, _i64, _i64, _i64, _i64, _p, _i64, _p, _i64, _p, _p, _i32, _p]),
     "bnn_conv2d": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p, _p, _p, _p, _sz, _p]),
     "bnn_conv2d_workspace_bytes": (_sz, [_i32] * 10),
+    "bnn_conv2d_packed": (_i32, [_p, _p] + [_i32] * 12 + [_p, _p, _p, _p, _p, _p]),
+    "bnn_conv2d_f32_sign": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p, _p, _p]),
+    "bnn_pack_fc_weight_nhwc": (_i32, [_p, _i64, _i32, _i32, _i32, _p, _p]),
     "bnn_maxpool2x2": (_i32, [_p, _i32, _i32, _i32, _i32, _p, _p, _p, _p, _p]),
     "bnn_conv2d_f32": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p, _p, _p]),
     "bnn_fc_f32": (_i32, [_p, _p, _p, _i64, _i64, _i64, _i32, _p, _p]),
@@ -197,6 +200,55 @@ def bnn_conv2d(x: torch.Tensor, w_packed: torch.Tensor, D: int, kH: int, kW: int
                             _ptr(out_i32), _ptr(out_f32), _ptr(scale), _ptr(bias), _ptr(workspace),
                             workspace.numel(), _stream()), "bnn_conv2d")
     return out_i32, out_f32
+
+
+def bnn_conv2d_packed(xp: torch.Tensor, w_packed: torch.Tensor, C: int, D: int, kH: int, kW: int, stride=(1, 1),
+                      pad=(0, 0), pool: int = 0, scale: Optional[torch.Tensor] = None,
+                      bias: Optional[torch.Tensor] = None, out: str = "packed", out_buf: Optional[torch.Tensor] = None):
+    """xp: packed NHWC [N, H, W, Cw] (int64-typed).  out = "packed" | "i32" | "f32"."""
+    _dev(xp, torch.int64, "x_packed")
+    _dev(w_packed, torch.int64, "w_packed")
+    assert xp.dim() == 4 and xp.is_contiguous() and w_packed.is_contiguous()
+    N, H, W, Cw = xp.shape
+    assert Cw == packed_words(C)
+    OH, OW = conv_out_dim(H, kH, stride[0], pad[0]), conv_out_dim(W, kW, stride[1], pad[1])
+    oi = of = op = None
+    if out == "packed":
+        op = out_buf if out_buf is not None else torch.empty(
+            (N, OH // 2 if pool else OH, OW // 2 if pool else OW, packed_words(D)), dtype=torch.int64, device=xp.device)
+    elif out == "i32":
+        oi = out_buf if out_buf is not None else torch.empty((N, D, OH, OW), dtype=torch.int32, device=xp.device)
+    elif out == "f32":
+        of = out_buf if out_buf is not None else torch.empty((N, D, OH, OW), dtype=torch.float32, device=xp.device)
+    else:
+        raise ValueError(out)
+    _check(lib().bnn_conv2d_packed(_ptr(xp), _ptr(w_packed), N, C, H, W, D, kH, kW, stride[0], stride[1], pad[0],
+                                   pad[1], pool, _ptr(oi), _ptr(of), _ptr(op), _ptr(scale), _ptr(bias), _stream()),
+           "bnn_conv2d_packed")
+    return op if op is not None else (oi if oi is not None else of)
+
+
+def bnn_conv2d_f32_sign(x: torch.Tensor, w: torch.Tensor, scale: torch.Tensor, bias: torch.Tensor, stride=(1, 1),
+                        pad=(0, 0), out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    _dev(x, torch.float32, "x")
+    _dev(w, torch.float32, "w")
+    N, C, H, W = x.shape
+    D, _, kH, kW = w.shape
+    OH, OW = conv_out_dim(H, kH, stride[0], pad[0]), conv_out_dim(W, kW, stride[1], pad[1])
+    if out is None:
+        out = torch.empty((N, OH, OW, packed_words(D)), dtype=torch.int64, device=x.device)
+    _check(lib().bnn_conv2d_f32_sign(_ptr(x), _ptr(w), N, C, H, W, D, kH, kW, stride[0], stride[1], pad[0], pad[1],
+                                     _ptr(scale), _ptr(bias), _ptr(out), _stream()), "bnn_conv2d_f32_sign")
+    return out
+
+
+def bnn_pack_fc_weight_nhwc(w: torch.Tensor, C: int, H: int, W: int) -> torch.Tensor:
+    _dev(w, torch.float32, "w")
+    assert w.dim() == 2 and w.is_contiguous() and w.shape[1] == C * H * W
+    out = torch.empty((w.shape[0], H * W * packed_words(C)), dtype=torch.int64, device=w.device)
+    _check(lib().bnn_pack_fc_weight_nhwc(_ptr(w), w.shape[0], C, H, W, _ptr(out), _stream()),
+           "bnn_pack_fc_weight_nhwc")
+    return out
 
 
 def bnn_maxpool2x2(a: torch.Tensor, scale: Optional[torch.Tensor] = None, bias: Optional[torch.Tensor] = None,

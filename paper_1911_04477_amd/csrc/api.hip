@@ -113,6 +113,7 @@ extern "C" const char *bnn_kernel_name(int kernel_id) {
     case bnn::KID_XNOR_GEMM_SMALL: return "xnor_gemm_small";
     case bnn::KID_MAXPOOL: return "maxpool2x2";
     case bnn::KID_CONV_F32: return "conv2d_f32";
+    case bnn::KID_CONV_F32_SIGN: return "conv2d_f32_sign";
     case bnn::KID_FC_F32: return "fc_f32";
     case bnn::KID_VALU_PROBE: return "valu_probe";
     case bnn::KID_COPY_PROBE: return "copy_probe";

@@ -20,7 +20,8 @@ enum KernelId : int {
   KID_VALU_PROBE = 8,
   KID_COPY_PROBE = 9,
   KID_XNOR_GEMM_SMALL = 10,
-  KID_COUNT = 11
+  KID_CONV_F32_SIGN = 11,
+  KID_COUNT = 12
 };
 
 // Timing hook: records an event pair around a launch when profiling is on.
@@ -66,9 +67,20 @@ __device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) {
 }
 
 // ---- cross-file internals ---------------------------------------------------------------
+// Geometry of an implicit-GEMM B operand: column n of the GEMM is output pixel n of a
+// convolution over a packed NHWC image (ceil(C/64) words per pixel), and word w of its
+// row is word (w mod Cw) of tap (w div Cw), taps ordered (kh, kw).
+struct ConvGeom {
+  const uint64_t *act;  // [Nimg, H, W, Cw]
+  int C, H, W, Cw, OH, OW, kW, sH, sW, pH, pW;
+  int pool;             // 0, or 2: columns are ordered window-major (see decode_col in gemm.hip)
+  FastDiv divCw, divKW;
+  FastDiv divOW, divOH; // output dims, or pooled output dims when pool == 2
+};
+
 struct GemmParams {
   const uint32_t *A;   // [M, lda32] dwords
-  const uint64_t *B;   // [N, ldb] words
+  const uint64_t *B;   // [N, ldb] words (explicit B only)
   int64_t lda32, ldb;
   int M, N;
   int Kd;              // dwords per row that hold bits of the reduction (ceil(Kbits/32))
@@ -85,12 +97,15 @@ struct GemmParams {
   FastDiv divOHW;
   int64_t img_stride;  // elements between images in C / Y
   int tilesM, tilesN;
-  int dbg;
+  ConvGeom g;          // implicit B only
+  uint64_t *outp;      // packed-sign output [pixels, cw_out] (packed epilogue only)
+  int cw_out;
 };
 
-
 // Launch the exclusive-or / popcount GEMM described by p (tilesM / tilesN are filled in).
-bnn_status run_gemm(GemmParams &p, hipStream_t s);
+// bmode 0: B is an explicit [N, ldb] matrix; 1: B is gathered from p.g (implicit GEMM).
+// emode 0: int32 / fp32 store; 1: packed sign(fma(scale, acc, bias)) store, optional 2x2 pool.
+bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s);
 
 // Conv helpers (im2col.hip).  check_conv_geometry validates shapes and 32-bit limits;
 // run_im2col launches encode (+ gather) with already validated arguments.

@@ -1,8 +1,169 @@
-// Binarized convolution driver: the forward graph of Figure 3 of the paper
-// (im2col + encode of the input, pre-encoded weight, Xnor-Bitcount, reshape to the
-// output feature map).  The reshape (col2im of section 2.1) costs nothing here: the GEMM
-// store writes each accumulator straight to its NCHW position.
+// Binarized convolution drivers: the forward graph of Figure 3 of the paper (encode the
+// input, pre-encoded weight, Xnor-Bitcount, reshape to the output feature map).
+//  * The reshape (col2im of section 2.1) costs nothing: the GEMM store writes each
+//    accumulator straight to its NCHW position.
+//  * The patch matrix of im2col is never materialised: the GEMM gathers its B tiles from
+//    the packed NHWC image (implicit GEMM).
+//  * bnn_conv2d_packed keeps activations packed between layers: packed NHWC in, and with
+//    the binarizing epilogue packed NHWC out (2x2 max-pool, affine map and sign fused into
+//    the GEMM store), so a stack of binarized layers moves 1 bit per activation.
+//  * bnn_conv2d_f32_sign is the real-valued first layer producing that packed format.
 #include "common.h"
+
+namespace bnn {
+
+bnn_status launch_encode_nchw(const float *x, int N, int C, int H, int W, int OHp, int OWp, int sH, int sW,
+                              uint64_t *out, hipStream_t s);
+
+static void fill_geom(ConvGeom &g, const uint64_t *act, int C, int H, int W, int kH, int kW, int sH, int sW, int pH,
+                      int pW, int pool) {
+  g.act = act;
+  g.C = C; g.H = H; g.W = W;
+  g.Cw = (int)bnn_packed_words(C);
+  g.OH = (int)bnn_conv_out_dim(H, kH, sH, pH);
+  g.OW = (int)bnn_conv_out_dim(W, kW, sW, pW);
+  g.kW = kW; g.sH = sH; g.sW = sW; g.pH = pH; g.pW = pW;
+  g.pool = pool;
+  g.divCw = FastDiv((uint32_t)g.Cw);
+  g.divKW = FastDiv((uint32_t)kW);
+  g.divOW = FastDiv((uint32_t)(pool ? g.OW / 2 : g.OW));
+  g.divOH = FastDiv((uint32_t)(pool ? g.OH / 2 : g.OH));
+}
+
+// GEMM over an already packed NHWC image; arguments validated by the callers.
+static bnn_status conv_from_packed(const uint64_t *act, const uint64_t *w_packed, int N, int C, int H, int W, int D,
+                                   int kH, int kW, int sH, int sW, int pH, int pW, int pool, int32_t *out_i32,
+                                   float *out_f32, uint64_t *out_packed, const float *scale, const float *bias,
+                                   hipStream_t s) {
+  const int64_t OH = bnn_conv_out_dim(H, kH, sH, pH), OW = bnn_conv_out_dim(W, kW, sW, pW);
+  const int64_t Kw = bnn_conv_kwords(C, kH, kW);
+  const int64_t cols = pool ? 4 * ((int64_t)N * (OH / 2) * (OW / 2)) : (int64_t)N * OH * OW;
+  GemmParams p = {};
+  p.A = reinterpret_cast<const uint32_t *>(w_packed);
+  p.B = nullptr;
+  p.lda32 = 2 * Kw;
+  p.ldb = Kw;
+  p.M = D;
+  p.N = (int)cols;
+  p.Kbits = (int)(Kw * 64);  // pad bits are 0 in both operands: they cancel in the exclusive-or
+  p.Kformula = C * kH * kW;
+  p.Kd = (int)(Kw * 2);
+  p.Kw64 = (int)Kw;
+  p.b_vec16 = 0;
+  p.C = out_i32;
+  p.Y = out_f32;
+  p.ldc = p.ldy = OH * OW;
+  p.scale = scale;
+  p.bias = bias;
+  p.axis = BNN_CH_ROW;
+  p.OHW = (uint32_t)(OH * OW);
+  p.divOHW = FastDiv((uint32_t)(OH * OW));
+  p.img_stride = (int64_t)D * OH * OW;
+  fill_geom(p.g, act, C, H, W, kH, kW, sH, sW, pH, pW, pool);
+  p.outp = out_packed;
+  p.cw_out = (int)bnn_packed_words(D);
+  return run_gemm(p, 1, out_packed ? 1 : 0, s);
+}
+
+static bnn_status conv_limits(int N, int C, int H, int W, int D, int kH, int kW, int sH, int sW, int pH, int pW) {
+  const int64_t OH = bnn_conv_out_dim(H, kH, sH, pH), OW = bnn_conv_out_dim(W, kW, sW, pW);
+  const int64_t P = (int64_t)N * OH * OW;
+  const int64_t Kw = bnn_conv_kwords(C, kH, kW);
+  if (P > 0x7ffffff0LL / 4 || (int64_t)D * 8 * Kw > 0xffffffffLL || (int64_t)D * P > 0x7fffffffLL * 8 ||
+      (int64_t)N * H * W > 0x7fffffffLL)
+    return BNN_ERR_UNSUPPORTED;
+  return BNN_OK;
+}
+
+// ---- real-valued first layer with binarized, packed output ----------------------------------
+// One thread per output pixel.  The input patch (K = C*kH*kW <= 32 taps) sits in registers,
+// the filter bank, scale and bias in LDS (read with wave-uniform addresses, i.e. broadcast).
+// Every output channel is the sequential fma chain over (c, kh, kw), then fma(scale, acc,
+// bias); only its sign is kept, 64 channels per stored word.
+constexpr int F32S_KMAX = 32;
+__global__ __launch_bounds__(256) void conv2d_f32_sign_kernel(const float *__restrict__ x, const float *__restrict__ w,
+                                                              int C, int H, int W, int D, int kH, int kW, int sH,
+                                                              int sW, int pH, int pW, int OH, int OW,
+                                                              const float *__restrict__ scale,
+                                                              const float *__restrict__ bias,
+                                                              uint64_t *__restrict__ outp, int cw_out, FastDiv divOW,
+                                                              FastDiv divOH, uint32_t total_pix, int K, int Kp) {
+  extern __shared__ float smem[];
+  float *sWt = smem;              // [D][Kp], Kp = K rounded up to 4
+  float *sSc = smem + D * Kp;     // [D]
+  float *sBi = sSc + D;           // [D]
+  for (int idx = threadIdx.x; idx < D * Kp; idx += 256) {
+    const int d = idx / Kp, k = idx - d * Kp;
+    sWt[idx] = k < K ? w[(size_t)d * K + k] : 0.0f;
+  }
+  for (int d = threadIdx.x; d < D; d += 256) {
+    sSc[d] = scale[d];
+    sBi[d] = bias[d];
+  }
+  __syncthreads();
+  const uint32_t p = blockIdx.x * 256u + threadIdx.x;
+  if (p >= total_pix) return;
+  const uint32_t t = fdiv(p, divOW);
+  const uint32_t ow = p - t * OW;
+  const uint32_t n = fdiv(t, divOH);
+  const uint32_t oh = t - n * OH;
+  const int ih0 = (int)(oh * sH) - pH, iw0 = (int)(ow * sW) - pW;
+  const float *xn = x + (size_t)n * C * H * W;
+  const int taps = kH * kW;
+  float xv[F32S_KMAX];
+#pragma unroll
+  for (int k = 0; k < F32S_KMAX; ++k) {
+    float v = 0.0f;
+    if (k < K) {
+      const int c = k / taps, r = k - c * taps;
+      const int kh = r / kW, kw = r - kh * kW;
+      const int ih = ih0 + kh, iw = iw0 + kw;
+      if (ih >= 0 && ih < H && iw >= 0 && iw < W) v = xn[((size_t)c * H + ih) * W + iw];
+    }
+    xv[k] = v;
+  }
+  for (int d0 = 0; d0 < D; d0 += 64) {
+    uint32_t lo = 0, hi = 0;
+    const int dn = D - d0 < 64 ? D - d0 : 64;
+    for (int dd = 0; dd < dn; ++dd) {
+      const float4 *wr = reinterpret_cast<const float4 *>(sWt + (size_t)(d0 + dd) * Kp);
+      float acc = 0.0f;
+#pragma unroll
+      for (int k4 = 0; k4 < F32S_KMAX / 4; ++k4) {
+        if (4 * k4 < K) {
+          const float4 w4 = wr[k4];
+          acc = fmaf(xv[4 * k4], w4.x, acc);
+          if (4 * k4 + 1 < K) acc = fmaf(xv[4 * k4 + 1], w4.y, acc);
+          if (4 * k4 + 2 < K) acc = fmaf(xv[4 * k4 + 2], w4.z, acc);
+          if (4 * k4 + 3 < K) acc = fmaf(xv[4 * k4 + 3], w4.w, acc);
+        }
+      }
+      const uint32_t bit = fmaf(sSc[d0 + dd], acc, sBi[d0 + dd]) >= 0.0f ? 1u : 0u;
+      if (dd < 32) lo |= bit << dd; else hi |= bit << (dd - 32);
+    }
+    outp[(size_t)p * cw_out + (d0 >> 6)] = ((uint64_t)hi << 32) | lo;
+  }
+}
+
+// Filter bank of a fully-connected layer whose input is a flattened NCHW map [C, H, W],
+// re-ordered to the packed NHWC bit order (h, w, c) of the activations: a common
+// permutation of the reduction axis leaves the result unchanged.
+__global__ __launch_bounds__(256) void pack_fc_weight_nhwc_kernel(const float *__restrict__ w, int C, int HW, int Cw,
+                                                                  uint64_t *__restrict__ out, int64_t total_words) {
+  const int lane = threadIdx.x & 63;
+  const int64_t g = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (g >= total_words) return;
+  const int cw = (int)(g % Cw);
+  const int hw = (int)((g / Cw) % HW);
+  const int64_t n = g / ((int64_t)Cw * HW);
+  const int c = cw * 64 + lane;
+  float v = -1.0f;
+  if (c < C) v = w[(n * C + c) * HW + hw];
+  const uint64_t m = __ballot(v >= 0.0f);
+  if (lane == 0) out[g] = m;
+}
+
+}  // namespace bnn
 
 using namespace bnn;
 
@@ -21,38 +182,91 @@ extern "C" bnn_status bnn_conv2d(const float *x, const uint64_t *w_packed, int N
     return BNN_ERR_ALIGN;
   const size_t need = bnn_conv2d_workspace_bytes(N, C, H, W, kH, kW, sH, sW, pH, pW);
   if (workspace_bytes < need) return BNN_ERR_WORKSPACE;
-  const int64_t OH = bnn_conv_out_dim(H, kH, sH, pH), OW = bnn_conv_out_dim(W, kW, sW, pW);
-  const int64_t P = (int64_t)N * OH * OW;
-  const int64_t Kw = bnn_conv_kwords(C, kH, kW);
-  if (P > 0x7ffffff0LL || (int64_t)D * 8 * Kw > 0xffffffffLL || (int64_t)D * P > 0x7fffffffLL * 8)
-    return BNN_ERR_UNSUPPORTED;
-  hipStream_t s = (hipStream_t)stream;
-
-  const size_t img_bytes = bnn_im2col_workspace_bytes(N, C, H, W, kH, kW, sH, sW, pH, pW);
-  uint64_t *cols = reinterpret_cast<uint64_t *>(static_cast<char *>(workspace) + img_bytes);
-  st = run_im2col(x, N, C, H, W, kH, kW, sH, sW, pH, pW, cols, workspace, s);
+  st = conv_limits(N, C, H, W, D, kH, kW, sH, sW, pH, pW);
   if (st != BNN_OK) return st;
+  hipStream_t s = (hipStream_t)stream;
+  uint64_t *img = reinterpret_cast<uint64_t *>(workspace);
+  if (kH == 1 && kW == 1 && pH == 0 && pW == 0) {
+    // no patch expansion: encode only the sampled pixels, then a stride-1 1x1 problem on them
+    const int OH = (int)bnn_conv_out_dim(H, 1, sH, 0), OW = (int)bnn_conv_out_dim(W, 1, sW, 0);
+    st = launch_encode_nchw(x, N, C, H, W, OH, OW, sH, sW, img, s);
+    if (st != BNN_OK) return st;
+    return conv_from_packed(img, w_packed, N, C, OH, OW, D, 1, 1, 1, 1, 0, 0, 0, out_i32, out_f32, nullptr, scale,
+                            bias, s);
+  }
+  st = launch_encode_nchw(x, N, C, H, W, H, W, 1, 1, img, s);
+  if (st != BNN_OK) return st;
+  return conv_from_packed(img, w_packed, N, C, H, W, D, kH, kW, sH, sW, pH, pW, 0, out_i32, out_f32, nullptr, scale,
+                          bias, s);
+}
 
-  GemmParams p;
-  p.A = reinterpret_cast<const uint32_t *>(w_packed);
-  p.B = cols;
-  p.lda32 = 2 * Kw;
-  p.ldb = Kw;
-  p.M = D;
-  p.N = (int)P;
-  p.Kbits = (int)(Kw * 64);  // pad bits are 0 in both operands: they cancel in the exclusive-or
-  p.Kformula = C * kH * kW;
-  p.Kd = (int)(Kw * 2);
-  p.Kw64 = (int)Kw;
-  p.b_vec16 = (Kw % 2 == 0) ? 1 : 0;
-  p.C = out_i32;
-  p.Y = out_f32;
-  p.ldc = p.ldy = OH * OW;
-  p.scale = scale;
-  p.bias = bias;
-  p.axis = BNN_CH_ROW;
-  p.OHW = (uint32_t)(OH * OW);
-  p.divOHW = FastDiv((uint32_t)(OH * OW));
-  p.img_stride = (int64_t)D * OH * OW;
-  return run_gemm(p, s);
+extern "C" bnn_status bnn_conv2d_packed(const uint64_t *x_packed, const uint64_t *w_packed, int N, int C, int H, int W,
+                                        int D, int kH, int kW, int sH, int sW, int pH, int pW, int pool,
+                                        int32_t *out_i32, float *out_f32, uint64_t *out_packed, const float *scale,
+                                        const float *bias, void *stream) {
+  bnn_status st = check_conv_geometry(N, C, H, W, kH, kW, sH, sW, pH, pW);
+  if (st != BNN_OK) return st;
+  if (D < 0 || (pool != 0 && pool != 2)) return BNN_ERR_SHAPE;
+  const int64_t OH = bnn_conv_out_dim(H, kH, sH, pH), OW = bnn_conv_out_dim(W, kW, sW, pW);
+  if (pool == 2 && ((OH & 1) || (OW & 1))) return BNN_ERR_SHAPE;
+  if (N == 0 || D == 0) return BNN_OK;
+  if (!x_packed || !w_packed || (!out_i32 && !out_f32 && !out_packed)) return BNN_ERR_NULL;
+  if ((out_f32 || out_packed) && (!scale || !bias)) return BNN_ERR_NULL;
+  if (out_packed && (out_i32 || out_f32)) return BNN_ERR_UNSUPPORTED;  // one kind of output per call
+  if (pool == 2 && !out_packed) return BNN_ERR_UNSUPPORTED;            // pooling lives in the packed epilogue
+  if (!aligned16(x_packed) || !aligned16(w_packed) || (out_i32 && !aligned16(out_i32)) ||
+      (out_f32 && !aligned16(out_f32)) || (out_packed && !aligned16(out_packed)))
+    return BNN_ERR_ALIGN;
+  st = conv_limits(N, C, H, W, D, kH, kW, sH, sW, pH, pW);
+  if (st != BNN_OK) return st;
+  return conv_from_packed(x_packed, w_packed, N, C, H, W, D, kH, kW, sH, sW, pH, pW, pool, out_i32, out_f32,
+                          out_packed, scale, bias, (hipStream_t)stream);
+}
+
+extern "C" bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N, int C, int H, int W, int D, int kH,
+                                          int kW, int sH, int sW, int pH, int pW, const float *scale,
+                                          const float *bias, uint64_t *out_packed, void *stream) {
+  bnn_status st = check_conv_geometry(N, C, H, W, kH, kW, sH, sW, pH, pW);
+  if (st != BNN_OK) return st;
+  if (D < 0) return BNN_ERR_SHAPE;
+  if (N == 0 || D == 0) return BNN_OK;
+  if (!x || !w || !scale || !bias || !out_packed) return BNN_ERR_NULL;
+  if (!aligned16(x) || !aligned16(w) || !aligned16(out_packed)) return BNN_ERR_ALIGN;
+  const int64_t K = (int64_t)C * kH * kW;
+  const int64_t Kp = (K + 3) / 4 * 4;
+  const size_t lds = (size_t)(D * Kp + 2 * D) * sizeof(float);
+  if (K > F32S_KMAX || lds > 64 * 1024) return BNN_ERR_UNSUPPORTED;
+  const int64_t OH = bnn_conv_out_dim(H, kH, sH, pH), OW = bnn_conv_out_dim(W, kW, sW, pW);
+  const int64_t total = (int64_t)N * OH * OW;
+  if (total > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  {
+    ProfScope ps(KID_CONV_F32_SIGN, s);
+    hipLaunchKernelGGL(conv2d_f32_sign_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), lds, s, x, w, C, H, W,
+                       D, kH, kW, sH, sW, pH, pW, (int)OH, (int)OW, scale, bias, out_packed,
+                       (int)bnn_packed_words(D), FastDiv((uint32_t)OW), FastDiv((uint32_t)OH), (uint32_t)total, (int)K,
+                       (int)Kp);
+  }
+  return launch_status();
+}
+
+extern "C" bnn_status bnn_pack_fc_weight_nhwc(const float *w, int64_t Nout, int C, int H, int W, uint64_t *w_packed,
+                                              void *stream) {
+  if (Nout < 0 || C <= 0 || H <= 0 || W <= 0) return BNN_ERR_SHAPE;
+  if (Nout == 0) return BNN_OK;
+  if (!w || !w_packed) return BNN_ERR_NULL;
+  if (!aligned16(w) || !aligned16(w_packed)) return BNN_ERR_ALIGN;
+  const int64_t Cw = bnn_packed_words(C);
+  const int64_t HW = (int64_t)H * W;
+  if (HW > 0x7fffffffLL || Nout * C * HW > 0x7fffffffLL * 64) return BNN_ERR_UNSUPPORTED;
+  const int64_t total = Nout * HW * Cw;
+  const int64_t blocks = (total + 3) / 4;
+  if (blocks > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  {
+    ProfScope ps(KID_PACK_CONV_WEIGHT, s);
+    hipLaunchKernelGGL(pack_fc_weight_nhwc_kernel, dim3((unsigned)blocks), dim3(256), 0, s, w, C, (int)HW, (int)Cw,
+                       w_packed, total);
+  }
+  return launch_status();
 }

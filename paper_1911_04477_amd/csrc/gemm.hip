@@ -6,18 +6,26 @@
 // which adds its popcount into the accumulator).  The kernel is built so that the
 // inner loop is almost nothing else:
 //   * lanes of a wave run along N (64 consecutive columns per register column);
-//     every lane keeps TM x TN int32 accumulators;
-//   * the TM rows of A a wave works on are the same for all of its lanes, so A is
+//     every lane keeps 8 x TN int32 accumulators;
+//   * the 8 rows of A a wave works on are the same for all of its lanes, so A is
 //     fetched with SCALAR loads into SGPRs and enters v_xor as the scalar operand:
 //     no LDS traffic, no VGPRs and no VALU instructions are spent on A;
-//   * the block's B tile (BN columns x KC dwords) is staged once per K-chunk through
-//     LDS, row-per-column with a 4-dword pad so that both the 16-byte staging writes
-//     and the 16-byte per-lane reads are bank-conflict free; the next chunk's global
-//     loads are in flight while the current chunk is computed;
-//   * full chunks run a fully unrolled mask-free path; only the final partial chunk
-//     (K not a multiple of 32*KC) takes a per-dword path that masks the bits past K;
-//   * K - 2*acc, the optional fma(scale, acc, bias) and the NCHW scatter of a
-//     convolution happen once in the store, 256 contiguous bytes per wave store.
+//   * the block's B tile (BN columns x 8 dwords) is staged once per K-chunk through
+//     double-buffered LDS, row-per-column with a 4-dword pad so that both the 16-byte
+//     staging writes and the 16-byte per-lane reads are bank-conflict free; the next
+//     chunk's global loads are issued before the current chunk is computed and first
+//     touched after it;
+//   * B is either an explicit K-contiguous matrix or (implicit GEMM) gathered on the
+//     fly from a packed NHWC image: column = output pixel, row word = tap word, pad
+//     taps replaced by the "+1" word -- no patch matrix is ever written;
+//   * the last, partial chunk re-reads the final 8 dwords of the rows (a window that
+//     overlaps the previous chunk); the overlap and the bits past K are zeroed in both
+//     operands (A in SGPRs with scalar moves, B in the staging), so it runs the same
+//     instruction sequence as a full chunk;
+//   * the store does K - 2*acc and then either writes int32 / fma(scale, acc, bias) fp32
+//     (row-major or scattered to NCHW, 256 contiguous bytes per wave store), or -- the
+//     binarizing epilogue -- takes the 2x2 max (optional), applies the fma, keeps only the
+//     sign and writes packed NHWC words for the next layer (32x fewer output bytes).
 // Workgroup ids are remapped so that tiles sharing a B tile run on the same XCD
 // (one L2 per XCD; hardware deals consecutive ids round-robin over the 8 XCDs).
 #include "common.h"
@@ -26,18 +34,14 @@
 namespace bnn {
 
 using u32x4 = uint32_t __attribute__((ext_vector_type(4)));
-typedef u32x4 u32x4_a8 __attribute__((aligned(8)));
+using u32x8 = uint32_t __attribute__((ext_vector_type(8)));
 // A is only ever read by the kernel.  Reading it through the constant address space lets
-// the compiler use scalar (SMEM) loads for the wave-uniform addresses even after a barrier.
+// the compiler use scalar (SMEM) loads for wave-uniform addresses.
 #define BNN_CONST_AS __attribute__((address_space(4)))
 typedef const uint32_t BNN_CONST_AS *cu32_ptr;
-typedef const u32x4_a8 BNN_CONST_AS *cu32x4_ptr;
-
-using u32x8 = uint32_t __attribute__((ext_vector_type(8)));
 
 // acc += popcount(x) as ONE instruction.  Written as asm because the optimizer otherwise
-// re-associates a chain of popcount-adds into v_bcnt(x, 0) plus separate three-operand adds,
-// which costs 25 % more VALU instructions in the inner loop.
+// re-associates a chain of popcount-adds into v_bcnt(x, 0) plus separate three-operand adds.
 __device__ __forceinline__ int popc_acc(uint32_t x, int acc) {
   asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc) : "v"(x));
   return acc;
@@ -59,12 +63,42 @@ struct GemmCfg {
   static_assert(PIECES % THREADS == 0 || PIECES < THREADS, "staging must divide evenly");
 };
 
-template <int TN, int WM, int WN, int MINW>
+// words of a tap that lies outside the image: every real channel is +1 (bit 1)
+__device__ __forceinline__ uint64_t pad_word64(int C, int cw) {
+  const int left = C - cw * 64;
+  return left >= 64 ? ~0ull : (left <= 0 ? 0ull : ((1ull << left) - 1ull));
+}
+
+// Column n of an implicit GEMM -> output pixel.  Without pooling the columns are the
+// output pixels in NHWC order.  With 2x2 pooling a tile of 256 columns holds 64 pooling
+// windows: column 256*t + 64*j + l is member j (row-major in the 2x2 window) of window
+// 64*t + l, so that the four members of a window are the four register columns of one lane.
+__device__ __forceinline__ void decode_col(const ConvGeom &g, uint32_t n, uint32_t &img, int &oh, int &ow) {
+  if (g.pool == 0) {
+    const uint32_t t = fdiv(n, g.divOW);
+    ow = (int)(n - t * g.OW);
+    img = fdiv(t, g.divOH);
+    oh = (int)(t - img * g.OH);
+  } else {
+    const uint32_t j = (n >> 6) & 3u;
+    const uint32_t wdx = (n >> 8) * 64u + (n & 63u);
+    const uint32_t PW = g.OW >> 1, PH = g.OH >> 1;
+    const uint32_t t = fdiv(wdx, g.divOW);
+    const uint32_t wx = wdx - t * PW;
+    img = fdiv(t, g.divOH);
+    const uint32_t wy = t - img * PH;
+    oh = (int)(2 * wy + (j >> 1));
+    ow = (int)(2 * wx + (j & 1));
+  }
+}
+
+template <int TN, int WM, int WN, int MINW, int BMODE, int EMODE, int YIELD>
 __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParams p) {
   using Cfg = GemmCfg<TN, WM, WN>;
   constexpr int RS = Cfg::RS;
   constexpr int PPT = Cfg::PPT;
   constexpr int QPR = KC / 4;  // 16-byte pieces per row
+  static_assert(EMODE == 0 || (WM == 8 && WN == 1 && TN == 4), "packed epilogue needs the 64 x 256 tile");
   __shared__ __attribute__((aligned(16))) uint32_t sB[2 * Cfg::TILE];
 
   const int tid = threadIdx.x;
@@ -93,10 +127,10 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
     aoffb[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)m * (uint32_t)p.lda32 * 4u));
   }
   // 64-bit base of A in an SGPR pair (readfirstlane returns a signed int: each half is cast
-  // to unsigned before widening); advanced by one chunk (32 bytes) per iteration.
+  // to unsigned before widening).
   const uint32_t Abase_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)p.A);
   const uint32_t Abase_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uintptr_t)p.A >> 32));
-  uint64_t Abase = ((uint64_t)Abase_hi << 32) | (uint64_t)Abase_lo;
+  const uint64_t Abase0 = ((uint64_t)Abase_hi << 32) | (uint64_t)Abase_lo;
   const cu32_ptr Ac = (cu32_ptr)(uintptr_t)p.A;
 
   int acc[TM][TN];
@@ -105,83 +139,155 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
 #pragma unroll
     for (int j = 0; j < TN; ++j) acc[i][j] = 0;
 
-  const int nchunks = (p.Kd + KC - 1) / KC;     // chunks holding any bit
-  const int nfull = p.Kbits / (32 * KC);        // chunks whose every bit takes part (nchunks - nfull is 0 or 1)
+  // K bookkeeping (all wave-uniform).  Full chunks cover words [0, 4*nfull).  When bits
+  // remain and the row has at least 4 words, a last "window" chunk covers words
+  // [Kw64-4, Kw64); otherwise (K < 193 bits) the remainder is done one dword at a time.
+  const int nfull = p.Kbits / (32 * KC);
+  const int rem_bits = p.Kbits - nfull * 32 * KC;
+  const bool window = rem_bits > 0 && p.Kw64 >= 4;
+  const bool slow_tail = rem_bits > 0 && !window;
+  const int nstages = nfull + (rem_bits > 0 ? 1 : 0);
   const int last_w = p.Kw64 - 1;
   const int tail_bits = p.Kbits & 63;
   const uint64_t tail_mask = tail_bits ? ((1ull << tail_bits) - 1ull) : ~0ull;
+  // first word of stage s: 4*s for full chunks (and for the slow tail), Kw64-4 for the window
+  auto stage_word0 = [&](int s) { return (s == nfull && window) ? p.Kw64 - 4 : 4 * s; };
 
   // ---- staging: global -> registers -> LDS (double-buffered) -----------------------
+  // Per-slot constants of the implicit-GEMM gather (one output pixel per slot).
+  int s_ih0[PPT], s_iw0[PPT];
+  uint32_t s_pix0[PPT];
+  bool s_ok[PPT];
+  if constexpr (BMODE == 1) {
+#pragma unroll
+    for (int t = 0; t < PPT; ++t) {
+      const int idx = t * Cfg::THREADS + tid;
+      const int row = idx / QPR;
+      const uint32_t n = (uint32_t)(n0 + row);
+      // pooled ordering: a column is real iff its window exists (N = 4 * windows, but the
+      // columns of the last tile's missing windows are interleaved with real ones)
+      const uint32_t wdx = (n >> 8) * 64u + (n & 63u);
+      s_ok[t] = idx < Cfg::PIECES && (p.g.pool ? wdx < (uint32_t)(p.N >> 2) : n < (uint32_t)p.N);
+      uint32_t img = 0;
+      int oh = 0, ow = 0;
+      if (s_ok[t]) decode_col(p.g, n, img, oh, ow);
+      s_ih0[t] = oh * p.g.sH - p.g.pH;
+      s_iw0[t] = ow * p.g.sW - p.g.pW;
+      s_pix0[t] = img * (uint32_t)(p.g.H * p.g.W);
+    }
+  }
+  // One word of an implicit B row: tap = w / Cw, channel word = w % Cw.
+  auto gather_word = [&](int t, int w) -> uint64_t {
+    const uint32_t tap = fdiv((uint32_t)w, p.g.divCw);
+    const int cw = w - (int)tap * p.g.Cw;
+    const uint32_t kh = fdiv(tap, p.g.divKW);
+    const int kw = (int)(tap - kh * p.g.kW);
+    const int ih = s_ih0[t] + (int)kh, iw = s_iw0[t] + kw;
+    if (ih >= 0 && ih < p.g.H && iw >= 0 && iw < p.g.W)
+      return p.g.act[((size_t)s_pix0[t] + (size_t)(ih * p.g.W + iw)) * p.g.Cw + cw];
+    return pad_word64(p.g.C, cw);
+  };
+
   // stage_load only ISSUES the global loads (raw words stay in registers, nothing uses them
   // until stage_store a whole chunk of compute later), so their latency is never waited on.
   u32x4 stage[PPT];
-  auto stage_load = [&](int chunk) {
+  auto stage_load = [&](int s) {
+    const int wbase = stage_word0(s);
 #pragma unroll
     for (int t = 0; t < PPT; ++t) {
       const int idx = t * Cfg::THREADS + tid;
       const int row = idx / QPR, q = idx % QPR;
-      const int n = n0 + row;
-      const int w0 = chunk * (KC / 2) + 2 * q;
+      const int w0 = wbase + 2 * q;
       u32x4 v = {0u, 0u, 0u, 0u};
-      if (idx < Cfg::PIECES && n < p.N && w0 <= last_w) {
-        const uint64_t *src = p.B + (int64_t)n * p.ldb + w0;
-        if (p.b_vec16 && w0 + 1 <= last_w) {
-          v = *reinterpret_cast<const u32x4 *>(src);
-        } else {
-          const uint2 lo = *reinterpret_cast<const uint2 *>(src);
-          v.x = lo.x; v.y = lo.y;
-          if (w0 + 1 <= last_w) {
-            const uint2 hi = *reinterpret_cast<const uint2 *>(src + 1);
-            v.z = hi.x; v.w = hi.y;
+      if constexpr (BMODE == 0) {
+        const int n = n0 + row;
+        if (idx < Cfg::PIECES && n < p.N && w0 <= last_w) {
+          const uint64_t *src = p.B + (int64_t)n * p.ldb + w0;
+          if (p.b_vec16 && !(wbase & 1) && w0 + 1 <= last_w) {
+            v = *reinterpret_cast<const u32x4 *>(src);
+          } else {
+            const uint2 lo = *reinterpret_cast<const uint2 *>(src);
+            v.x = lo.x; v.y = lo.y;
+            if (w0 + 1 <= last_w) {
+              const uint2 hi = *reinterpret_cast<const uint2 *>(src + 1);
+              v.z = hi.x; v.w = hi.y;
+            }
+          }
+        }
+      } else {
+        if (s_ok[t] && w0 <= last_w) {
+          if (!(p.g.Cw & 1) && !(wbase & 1)) {
+            // both words of the piece belong to one tap: one 16-byte load
+            const uint32_t tap = fdiv((uint32_t)w0, p.g.divCw);
+            const int cw = w0 - (int)tap * p.g.Cw;
+            const uint32_t kh = fdiv(tap, p.g.divKW);
+            const int kw = (int)(tap - kh * p.g.kW);
+            const int ih = s_ih0[t] + (int)kh, iw = s_iw0[t] + kw;
+            if (ih >= 0 && ih < p.g.H && iw >= 0 && iw < p.g.W) {
+              v = *reinterpret_cast<const u32x4 *>(
+                  p.g.act + ((size_t)s_pix0[t] + (size_t)(ih * p.g.W + iw)) * p.g.Cw + cw);
+            } else {
+              const uint64_t x0 = pad_word64(p.g.C, cw), x1 = pad_word64(p.g.C, cw + 1);
+              v.x = (uint32_t)x0; v.y = (uint32_t)(x0 >> 32); v.z = (uint32_t)x1; v.w = (uint32_t)(x1 >> 32);
+            }
+          } else {
+            const uint64_t x0 = gather_word(t, w0);
+            const uint64_t x1 = w0 + 1 <= last_w ? gather_word(t, w0 + 1) : 0ull;
+            v.x = (uint32_t)x0; v.y = (uint32_t)(x0 >> 32); v.z = (uint32_t)x1; v.w = (uint32_t)(x1 >> 32);
           }
         }
       }
       stage[t] = v;
     }
   };
-  // Masks the bits past K in the row's last word, then writes the pieces to LDS buffer buf.
-  auto stage_store = [&](int buf, int chunk) {
+  // Zeroes the words a window chunk shares with the full chunks before it, masks the bits
+  // past K in the row's last word, then writes the pieces to LDS buffer buf.
+  auto stage_store = [&](int buf, int s) {
+    const int wbase = stage_word0(s);
+    const int wdone = (s == nfull && window) ? 4 * nfull : 0;  // words below this are already counted
     const uint32_t tm_lo = (uint32_t)tail_mask, tm_hi = (uint32_t)(tail_mask >> 32);
 #pragma unroll
     for (int t = 0; t < PPT; ++t) {
       const int idx = t * Cfg::THREADS + tid;
       const int row = idx / QPR, q = idx % QPR;
-      const int w0 = chunk * (KC / 2) + 2 * q;
+      const int w0 = wbase + 2 * q;
       u32x4 v = stage[t];
       if (w0 == last_w) { v.x &= tm_lo; v.y &= tm_hi; }
       if (w0 + 1 == last_w) { v.z &= tm_lo; v.w &= tm_hi; }
+      if (w0 < wdone) { v.x = 0u; v.y = 0u; }
+      if (w0 + 1 < wdone) { v.z = 0u; v.w = 0u; }
       if (idx < Cfg::PIECES) *reinterpret_cast<u32x4 *>(&sB[buf * Cfg::TILE + row * RS + q * 4]) = v;
     }
   };
 
   const int lane_row = (wn * 64 * TN + lane) * RS;
 
-  stage_load(0);
-  stage_store(0, 0);
+  if (nstages > 0) {
+    stage_load(0);
+    stage_store(0, 0);
+  }
   __syncthreads();
 
-  // ---- full chunks ---------------------------------------------------------------------
+  // ---- chunks ----------------------------------------------------------------------------
   // Per chunk: the wave's 8 rows of A arrive with 8 scalar loads of 8 dwords (64 SGPRs),
   // issued together with the LDS reads of B; one wait; then 2 * 8 * TN * 8 xor / popcount
   // instructions and nothing else.  Loads, wait and the per-row compute statements are
   // volatile inline asm, so their order in the instruction stream is the order written
   // here; the wait names every loaded SGPR as in/out operand, which orders all uses after
   // it.  The latency of one wave's loads is covered by the other waves on the SIMD.
-  for (int c = 0; c < nfull; ++c) {
-    const int buf = (p.dbg & 1) ? 0 : (c & 1);
-    const bool more = c + 1 < nchunks && !(p.dbg & 1);
+  const int nfast = nfull + (window ? 1 : 0);
+  for (int c = 0; c < nfast; ++c) {
+    const int buf = c & 1;
+    const bool more = c + 1 < nstages;
     if (more) stage_load(c + 1);
     const uint32_t *sBl = &sB[buf * Cfg::TILE + lane_row];
+    const bool is_window = c == nfull;  // only possible for the last iteration
+    const uint64_t Abase = Abase0 + (uint64_t)(uint32_t)stage_word0(c) * 8u;
     u32x8 a[TM];
     u32x8 b[TN];
-    if (!(p.dbg & 2) || c == 0) {
 #pragma unroll
     for (int i = 0; i < TM; ++i)
-      asm volatile("s_load_dwordx8 %0, %1, %2"
-                   : "=s"(a[i])
-                   : "s"(Abase), "s"(aoffb[i]));
-    }
-    Abase += KC * 4;
+      asm volatile("s_load_dwordx8 %0, %1, %2" : "=s"(a[i]) : "s"(Abase), "s"(aoffb[i]));
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       b[j].lo = *reinterpret_cast<const u32x4 *>(&sBl[j * 64 * RS]);
@@ -189,14 +295,34 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
     }
     asm volatile("s_waitcnt lgkmcnt(0)"
                  : "+s"(a[0]), "+s"(a[1]), "+s"(a[2]), "+s"(a[3]), "+s"(a[4]), "+s"(a[5]), "+s"(a[6]), "+s"(a[7]));
+    if (is_window) {
+      // dwords already counted by the full chunks, and the bits past K, leave A as zeros
+      const int dw_done = 2 * (4 * nfull - (p.Kw64 - 4));
+      const uint32_t m6 = (uint32_t)tail_mask, m7 = (uint32_t)(tail_mask >> 32);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int d = 0; d < 8; ++d)
+          if (d < dw_done) a[i][d] = 0u;
+        a[i][6] &= m6;
+        a[i][7] &= m7;
+      }
+    }
     uint32_t t0, t1;
 #define BNN_BV(j, d) b[j][d]
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      if constexpr (TN == 8) BNN_GEMM_ROW_8(acc[i], a[i], BNN_BV, t0, t1);
-      else if constexpr (TN == 4) BNN_GEMM_ROW_4(acc[i], a[i], BNN_BV, t0, t1);
-      else if constexpr (TN == 2) BNN_GEMM_ROW_2(acc[i], a[i], BNN_BV, t0, t1);
-      else BNN_GEMM_ROW_1(acc[i], a[i], BNN_BV, t0, t1);
+      if constexpr (YIELD) {
+        if constexpr (TN == 8) BNN_GEMM_ROW_8(acc[i], a[i], BNN_BV, t0, t1);
+        else if constexpr (TN == 4) BNN_GEMM_ROW_4(acc[i], a[i], BNN_BV, t0, t1);
+        else if constexpr (TN == 2) BNN_GEMM_ROW_2(acc[i], a[i], BNN_BV, t0, t1);
+        else BNN_GEMM_ROW_1(acc[i], a[i], BNN_BV, t0, t1);
+      } else {
+        if constexpr (TN == 8) BNN_GEMM_ROW_8_NY(acc[i], a[i], BNN_BV, t0, t1);
+        else if constexpr (TN == 4) BNN_GEMM_ROW_4_NY(acc[i], a[i], BNN_BV, t0, t1);
+        else if constexpr (TN == 2) BNN_GEMM_ROW_2_NY(acc[i], a[i], BNN_BV, t0, t1);
+        else BNN_GEMM_ROW_1_NY(acc[i], a[i], BNN_BV, t0, t1);
+      }
     }
 #undef BNN_BV
     if (more) {
@@ -205,9 +331,9 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
     }
   }
 
-  // ---- final partial chunk (K not a multiple of 256 bits) ---------------------------------
-  // One dword at a time.  B is already masked / zero-filled by the staging; A is masked here.
-  if (nfull < nchunks) {
+  // ---- rows shorter than four words (K < 193): one dword at a time --------------------------
+  // B is already masked / zero-filled by the staging; A is masked here.
+  if (slow_tail) {
     const uint32_t *sBl = &sB[(nfull & 1) * Cfg::TILE + lane_row];
     const int kd0 = nfull * KC;
     const int tb32 = p.Kbits & 31;
@@ -232,73 +358,144 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   // slots) during the main loop.
   const GemmParams BNN_CONST_AS *kp = (const GemmParams BNN_CONST_AS *)__builtin_amdgcn_kernarg_segment_ptr();
   asm volatile("" : "+s"(kp));
-  const int M = kp->M, N = (kp->dbg & 4) ? 0 : kp->N, Kformula = kp->Kformula, axis = kp->axis;
-  int32_t *const Cp = kp->C;
-  float *const Yp = kp->Y;
+  const int M = kp->M, N = kp->N, Kformula = kp->Kformula;
   const float *const scale = kp->scale, *const bias = kp->bias;
-  const int64_t ldc = kp->ldc, ldy = kp->ldy, img_stride = kp->img_stride;
-  const uint32_t OHW = kp->OHW;
-  FastDiv divOHW;
-  divOHW.d = kp->divOHW.d; divOHW.mul = kp->divOHW.mul; divOHW.shift = kp->divOHW.shift;
 
-  const int nbase = n0 + wn * 64 * TN + lane;
+  if constexpr (EMODE == 0) {
+    const int axis = kp->axis;
+    int32_t *const Cp = kp->C;
+    float *const Yp = kp->Y;
+    const int64_t ldc = kp->ldc, ldy = kp->ldy, img_stride = kp->img_stride;
+    const uint32_t OHW = kp->OHW;
+    FastDiv divOHW;
+    divOHW.d = kp->divOHW.d; divOHW.mul = kp->divOHW.mul; divOHW.shift = kp->divOHW.shift;
+
+    const int nbase = n0 + wn * 64 * TN + lane;
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int n = nbase + j * 64;
-    if (n >= N) continue;
-    const uint32_t img = fdiv((uint32_t)n, divOHW);
-    const uint32_t pix = (uint32_t)n - img * OHW;
-    const int64_t coff = (int64_t)img * img_stride + pix + (int64_t)m0 * ldc;
-    const int64_t yoff = (int64_t)img * img_stride + pix + (int64_t)m0 * ldy;
-    int32_t *cp = Cp ? Cp + coff : nullptr;
-    float *yp = Yp ? Yp + yoff : nullptr;
-    float sc = 1.0f, bi = 0.0f;
-    if (Yp && axis == BNN_CH_COL) {
-      sc = scale[n];
-      bi = bias[n];
+    for (int j = 0; j < TN; ++j) {
+      const int n = nbase + j * 64;
+      if (n >= N) continue;
+      const uint32_t img = fdiv((uint32_t)n, divOHW);
+      const uint32_t pix = (uint32_t)n - img * OHW;
+      const int64_t coff = (int64_t)img * img_stride + pix + (int64_t)m0 * ldc;
+      const int64_t yoff = (int64_t)img * img_stride + pix + (int64_t)m0 * ldy;
+      int32_t *cp = Cp ? Cp + coff : nullptr;
+      float *yp = Yp ? Yp + yoff : nullptr;
+      float sc = 1.0f, bi = 0.0f;
+      if (Yp && axis == BNN_CH_COL) {
+        sc = scale[n];
+        bi = bias[n];
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        if (m0 + i < M) {
+          const int v = Kformula - 2 * acc[i][j];
+          if (cp) *cp = v;
+          if (yp) {
+            if (axis == BNN_CH_ROW) {
+              sc = scale[m0 + i];
+              bi = bias[m0 + i];
+            }
+            *yp = fmaf(sc, (float)v, bi);
+          }
+        }
+        if (cp) cp += ldc;
+        if (yp) yp += ldy;
+      }
     }
+  } else {
+    // Binarizing epilogue.  Row m is output channel m; the workgroup's 64 rows are exactly
+    // one 64-bit channel word (word index mi) of every pixel in its tile.  Each lane turns
+    // its 8 channels into a byte per output pixel, the 8 waves' bytes meet in LDS, and one
+    // thread per pixel writes the assembled word.
+    const int pool = kp->g.pool;
+    uint64_t *const outp = kp->outp;
+    const int cw_out = kp->cw_out;
+    uint32_t bytes[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bytes[j] = 0u;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-      if (m0 + i < M) {
-        const int v = Kformula - 2 * acc[i][j];
-        if (cp) *cp = v;
-        if (yp) {
-          if (axis == BNN_CH_ROW) {
-            sc = scale[m0 + i];
-            bi = bias[m0 + i];
-          }
-          *yp = fmaf(sc, (float)v, bi);
+      const int m = m0 + i;
+      const bool row_ok = m < M;
+      const float sc = row_ok ? scale[m] : 0.0f;
+      const float bi = row_ok ? bias[m] : -1.0f;  // rows past M give bit 0
+      if (pool) {
+        int v = Kformula - 2 * acc[i][0];
+#pragma unroll
+        for (int j = 1; j < TN; ++j) v = max(v, Kformula - 2 * acc[i][j]);
+        bytes[0] |= (uint32_t)(fmaf(sc, (float)v, bi) >= 0.0f) << i;
+      } else {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int v = Kformula - 2 * acc[i][j];
+          bytes[j] |= (uint32_t)(fmaf(sc, (float)v, bi) >= 0.0f) << i;
         }
       }
-      if (cp) cp += ldc;
-      if (yp) yp += ldy;
+    }
+    __syncthreads();  // every wave is done reading the B tiles: LDS is reused for the output bytes
+    uint8_t *sO = reinterpret_cast<uint8_t *>(sB);
+    if (pool) {
+      sO[lane * 8 + wm] = (uint8_t)bytes[0];
+    } else {
+#pragma unroll
+      for (int j = 0; j < TN; ++j) sO[(j * 64 + lane) * 8 + wm] = (uint8_t)bytes[j];
+    }
+    __syncthreads();
+    const int npix = pool ? 64 : 256;
+    if (tid < npix) {
+      const uint2 w = *reinterpret_cast<const uint2 *>(&sO[tid * 8]);
+      // global pixel index: pooled window index, or column index (NHWC pixel order)
+      const int64_t gp = pool ? (int64_t)ni * 64 + tid : (int64_t)n0 + tid;
+      const int64_t limit = pool ? (int64_t)(N >> 2) : (int64_t)N;
+      if (gp < limit) *reinterpret_cast<uint2 *>(outp + gp * cw_out + mi) = w;
     }
   }
 }
 
 // ---- host side ----------------------------------------------------------------------
+template <int TN, int WM, int WN, int MINW, int BMODE, int EMODE, int YIELD>
+static bnn_status launch_one(GemmParams &p, hipStream_t s, int kid) {
+  using Cfg = GemmCfg<TN, WM, WN>;
+  ProfScope ps(kid, s);
+  hipLaunchKernelGGL((xnor_gemm_kernel<TN, WM, WN, MINW, BMODE, EMODE, YIELD>),
+                     dim3((unsigned)(p.tilesM * p.tilesN)), dim3(Cfg::THREADS), 0, s, p);
+  return launch_status();
+}
+
 template <int TN, int WM, int WN, int MINW>
-static bnn_status launch_cfg(GemmParams &p, hipStream_t s, int kid) {
+static bnn_status launch_cfg(GemmParams &p, int bmode, int emode, hipStream_t s, int kid) {
   using Cfg = GemmCfg<TN, WM, WN>;
   p.tilesM = (p.M + Cfg::BM - 1) / Cfg::BM;
   p.tilesN = (p.N + Cfg::BN - 1) / Cfg::BN;
   const int64_t blocks = (int64_t)p.tilesM * p.tilesN;
   if (blocks > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
-  ProfScope ps(kid, s);
-  hipLaunchKernelGGL((xnor_gemm_kernel<TN, WM, WN, MINW>), dim3((unsigned)blocks), dim3(Cfg::THREADS), 0, s,
-                     p);
-  return launch_status();
+  // The one-cycle yields after each xor/popcount pair pay off only when at least two waves
+  // share a SIMD; with fewer they cost issue slots.  256 CUs x 4 SIMDs.
+  const int64_t waves = blocks * (Cfg::THREADS / 64);
+  const bool yield = waves >= 2 * 1024;
+  if constexpr (TN == 4 && WM == 8 && WN == 1) {
+    if (emode == 1) {
+      if (bmode != 1) return BNN_ERR_UNSUPPORTED;
+      return yield ? launch_one<TN, WM, WN, MINW, 1, 1, 1>(p, s, kid) : launch_one<TN, WM, WN, MINW, 1, 1, 0>(p, s, kid);
+    }
+  }
+  if (emode != 0) return BNN_ERR_UNSUPPORTED;
+  if (bmode == 1) {
+    if constexpr (TN == 8)
+      return BNN_ERR_UNSUPPORTED;
+    else
+      return yield ? launch_one<TN, WM, WN, MINW, 1, 0, 1>(p, s, kid) : launch_one<TN, WM, WN, MINW, 1, 0, 0>(p, s, kid);
+  }
+  return yield ? launch_one<TN, WM, WN, MINW, 0, 0, 1>(p, s, kid) : launch_one<TN, WM, WN, MINW, 0, 0, 0>(p, s, kid);
 }
 
 int g_force_cfg = -1;  // test / tuning hook: -1 = heuristic
-int g_dbg = 0;
 
-// Tile choice: the large tile (64 x 512) has the best ratio of VALU work to everything
-// else but needs enough tiles to fill 256 CUs twice over; smaller problems fall back to
-// finer tiles so that every CU has work.
-bnn_status run_gemm(GemmParams &p, hipStream_t s) {
+bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s) {
   int cfg = g_force_cfg;
-  p.dbg = g_dbg;
+  if (emode == 1) cfg = 3;                      // the packed epilogue is written for the 64 x 256 tile
+  if (bmode == 1 && (cfg == 0)) cfg = 3;        // no implicit-GEMM instantiation of the 32 x 512 tile
   if (cfg < 0) {
     // Measured on MI355X: 64 x 256 (TN = 4, eight waves per workgroup, six per SIMD) is the
     // fastest tile when there are enough of them; smaller problems take finer tiles so that
@@ -306,18 +503,15 @@ bnn_status run_gemm(GemmParams &p, hipStream_t s) {
     const int64_t t256 = (int64_t)((p.M + 63) / 64) * ((p.N + 255) / 256);
     const int64_t t128 = (int64_t)((p.M + 63) / 64) * ((p.N + 127) / 128);
     const int64_t t32 = (int64_t)((p.M + 31) / 32) * ((p.N + 127) / 128);
-    cfg = (p.M >= 64 && t256 >= 512) ? 3 : (p.M >= 64 && t128 >= 512) ? 6 : (t32 >= 256 ? 4 : 2);
+    cfg = (p.M >= 64 && t256 >= 512) ? 3 : (p.M >= 64 && t128 >= 512) ? 6 : (t32 >= 512 ? 4 : 2);
   }
   switch (cfg) {
-    case 0: return launch_cfg<8, 4, 1, 2>(p, s, KID_XNOR_GEMM);        // 32 x 512
-    case 1: return launch_cfg<4, 4, 1, 4>(p, s, KID_XNOR_GEMM);        // 32 x 256
-    case 2: return launch_cfg<1, 4, 1, 4>(p, s, KID_XNOR_GEMM_SMALL);  // 32 x 64
-    case 3: return launch_cfg<4, 8, 1, 4>(p, s, KID_XNOR_GEMM);        // 64 x 256
-    case 4: return launch_cfg<2, 4, 1, 4>(p, s, KID_XNOR_GEMM);        // 32 x 128
-    case 5: return launch_cfg<4, 16, 1, 4>(p, s, KID_XNOR_GEMM);       // 128 x 256
-    case 6: return launch_cfg<2, 8, 1, 4>(p, s, KID_XNOR_GEMM);        // 64 x 128
-    case 7: return launch_cfg<2, 16, 1, 4>(p, s, KID_XNOR_GEMM);       // 128 x 128
-    case 9: return launch_cfg<2, 4, 2, 4>(p, s, KID_XNOR_GEMM);        // 32 x 256 from TN = 2
+    case 0: return launch_cfg<8, 4, 1, 2>(p, bmode, emode, s, KID_XNOR_GEMM);        // 32 x 512
+    case 1: return launch_cfg<4, 4, 1, 4>(p, bmode, emode, s, KID_XNOR_GEMM);        // 32 x 256
+    case 2: return launch_cfg<1, 4, 1, 4>(p, bmode, emode, s, KID_XNOR_GEMM_SMALL);  // 32 x 64
+    case 3: return launch_cfg<4, 8, 1, 4>(p, bmode, emode, s, KID_XNOR_GEMM);        // 64 x 256
+    case 4: return launch_cfg<2, 4, 1, 4>(p, bmode, emode, s, KID_XNOR_GEMM);        // 32 x 128
+    case 6: return launch_cfg<2, 8, 1, 4>(p, bmode, emode, s, KID_XNOR_GEMM);        // 64 x 128
     default: return BNN_ERR_UNSUPPORTED;
   }
 }
@@ -337,7 +531,7 @@ static bnn_status gemm_common(const uint64_t *A, int64_t lda, const uint64_t *B,
   if (!aligned16(A) || !aligned16(B) || (C && !aligned16(C)) || (Y && !aligned16(Y))) return BNN_ERR_ALIGN;
   if (M > 0x7fffffffLL || N > 0x7ffffff0LL || K > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   if (M * 8 * lda > 0xffffffffLL) return BNN_ERR_UNSUPPORTED;  // 32-bit byte offsets into A
-  GemmParams p;
+  GemmParams p = {};
   p.A = reinterpret_cast<const uint32_t *>(A);
   p.B = B;
   p.lda32 = 2 * lda;
@@ -359,7 +553,7 @@ static bnn_status gemm_common(const uint64_t *A, int64_t lda, const uint64_t *B,
   p.OHW = 0x7fffffffu;
   p.divOHW = FastDiv(0x7fffffffu);
   p.img_stride = 0;
-  return run_gemm(p, (hipStream_t)stream);
+  return run_gemm(p, 0, 0, (hipStream_t)stream);
 }
 
 }  // namespace bnn
@@ -380,4 +574,3 @@ extern "C" bnn_status bnn_xnor_gemm_epilogue(const uint64_t *A, int64_t lda, con
 
 // Tuning / test hook (not declared in the public header): force a tile configuration.
 extern "C" void bnn_internal_force_gemm_cfg(int cfg) { g_force_cfg = cfg; }
-extern "C" void bnn_internal_gemm_dbg(int d) { g_dbg = d; }

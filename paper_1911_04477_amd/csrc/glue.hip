@@ -174,7 +174,8 @@ __global__ __launch_bounds__(256) void valu_probe_kernel(int32_t *__restrict__ s
 }
 
 // The GEMM's own per-row statements (8 rows x TN columns x 8 dwords) run from registers,
-// with no loads at all: the ceiling of that exact instruction sequence.
+// with no loads at all: the ceiling of that exact instruction sequence (V = 0 with the
+// one-cycle yield after each pair, V = 1 without).
 template <int TN, int V = 0>
 __global__ __launch_bounds__(256) void valu_rows_probe_kernel(int32_t *__restrict__ sink, int iters, uint32_t seed) {
   const uint32_t tid = blockIdx.x * 256u + threadIdx.x;
@@ -198,11 +199,10 @@ __global__ __launch_bounds__(256) void valu_rows_probe_kernel(int32_t *__restric
 #define BNN_BV(j, d) b[j][d]
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      if constexpr (TN == 4) BNN_GEMM_ROW_4(acc[i], a[i], BNN_BV, t0, t1);
-      else if constexpr (V == 1) BNN_GEMM_ROW_2_V1(acc[i], a[i], BNN_BV, t0, t1);
-      else if constexpr (V == 2) BNN_GEMM_ROW_2_V2(acc[i], a[i], BNN_BV, t0, t1);
-      else if constexpr (V == 3) BNN_GEMM_ROW_2_V3(acc[i], a[i], BNN_BV, t0, t1);
-      else BNN_GEMM_ROW_2(acc[i], a[i], BNN_BV, t0, t1);
+      if constexpr (TN == 4 && V == 0) BNN_GEMM_ROW_4(acc[i], a[i], BNN_BV, t0, t1);
+      else if constexpr (TN == 4) BNN_GEMM_ROW_4_NY(acc[i], a[i], BNN_BV, t0, t1);
+      else if constexpr (V == 0) BNN_GEMM_ROW_2(acc[i], a[i], BNN_BV, t0, t1);
+      else BNN_GEMM_ROW_2_NY(acc[i], a[i], BNN_BV, t0, t1);
     }
 #undef BNN_BV
 #pragma unroll
@@ -308,9 +308,8 @@ extern "C" bnn_status bnn_valu_peak_probe(int32_t *sink, int blocks, int iters, 
       // iters rounds of 8 x TN x 8 pairs: scale iters so that the lane-op count per launch matches
       case 5: hipLaunchKernelGGL(valu_rows_probe_kernel<2>, g, b, 0, s, sink, iters / 2, 1u); break;
       case 6: hipLaunchKernelGGL(valu_rows_probe_kernel<4>, g, b, 0, s, sink, iters / 4, 1u); break;
-      case 11: hipLaunchKernelGGL((valu_rows_probe_kernel<2, 1>), g, b, 0, s, sink, iters / 2, 1u); break;
-      case 12: hipLaunchKernelGGL((valu_rows_probe_kernel<2, 2>), g, b, 0, s, sink, iters / 2, 1u); break;
-      case 13: hipLaunchKernelGGL((valu_rows_probe_kernel<2, 3>), g, b, 0, s, sink, iters / 2, 1u); break;
+      case 7: hipLaunchKernelGGL((valu_rows_probe_kernel<2, 1>), g, b, 0, s, sink, iters / 2, 1u); break;
+      case 8: hipLaunchKernelGGL((valu_rows_probe_kernel<4, 1>), g, b, 0, s, sink, iters / 4, 1u); break;
       default: hipLaunchKernelGGL(valu_probe_kernel<0>, g, b, 0, s, sink, iters, 1u); break;
     }
   }

@@ -75,3 +75,63 @@ class VggStack:
             if keep:
                 acts.append(h.clone())
         return (h, acts) if keep else h
+
+
+class VggStackFused:
+    """The same stack with activations kept packed between layers (1 bit per activation):
+    real-valued first layer with binarized output, binarized convolutions whose GEMM store
+    does max-pool + affine + sign + pack, and the binarized FC on the packed map with its
+    weight re-ordered to the (h, w, c) bit order.  Same arithmetic, same results."""
+
+    def __init__(self, layers: Sequence, params: Sequence[Dict[str, np.ndarray]], batch: int, device="cuda:0"):
+        self.layers = list(layers)
+        self.batch = batch
+        self.dev = torch.device(device)
+        self.p: List[Dict[str, torch.Tensor]] = []
+        self.buf: List[Dict[str, torch.Tensor]] = []
+        hw_c = None  # (C, H, W) of the map entering the binarized FC
+        for L, prm in zip(self.layers, params):
+            d = {k: torch.from_numpy(np.ascontiguousarray(v)).to(self.dev) for k, v in prm.items()}
+            b: Dict[str, torch.Tensor] = {}
+            if L.kind == "conv_f32":
+                b["yp"] = torch.empty((batch, L.hw, L.hw, B.packed_words(L.cout)), dtype=torch.int64, device=self.dev)
+                hw_c = (L.cout, L.hw, L.hw)
+            elif L.kind == "bconv":
+                d["wp"] = B.bnn_pack_conv_weight(d["w"])
+                o = L.hw // 2 if L.pool else L.hw
+                b["yp"] = torch.empty((batch, o, o, B.packed_words(L.cout)), dtype=torch.int64, device=self.dev)
+                hw_c = (L.cout, o, o)
+            elif L.kind == "bfc":
+                C, H, W = hw_c
+                assert C * H * W == L.cin
+                d["wp"] = B.bnn_pack_fc_weight_nhwc(d["w"], C, H, W)
+                d["kbits"] = H * W * B.packed_words(C) * 64
+                d["ktrue"] = L.cin
+            elif L.kind == "fc_f32":
+                b["y"] = torch.empty((batch, L.cout), dtype=torch.float32, device=self.dev)
+            self.p.append(d)
+            self.buf.append(b)
+        torch.cuda.synchronize(self.dev)
+
+    def forward(self, x: torch.Tensor, keep: bool = False):
+        h = x
+        acts = []
+        for L, p, b in zip(self.layers, self.p, self.buf):
+            if L.kind == "conv_f32":
+                h = B.bnn_conv2d_f32_sign(h, p["w"], p["scale"], p["bias"], (1, 1), (1, 1), out=b["yp"])
+            elif L.kind == "bconv":
+                h = B.bnn_conv2d_packed(h, p["wp"], L.cin, L.cout, 3, 3, (1, 1), (1, 1), pool=2 if L.pool else 0,
+                                        scale=p["scale"], bias=p["bias"], out="packed", out_buf=b["yp"])
+            elif L.kind == "bfc":
+                # pad bits are 0 in both operands, so the GEMM runs over whole words and the
+                # formula takes the true K through the epilogue entry point's K argument
+                rows = h.view(self.batch, -1)
+                assert rows.shape[1] * 64 == p["kbits"] == p["ktrue"], "channel counts here are multiples of 64"
+                _, h = B.bnn_xnor_gemm_epilogue(rows, p["wp"], p["ktrue"], p["scale"], p["bias"], B.CH_COL)
+            elif L.kind == "fc_f32":
+                h = B.bnn_fc_f32(h.view(self.batch, -1), p["w"], p["bias"], sign_input=True, out=b["y"])
+            else:
+                raise ValueError(L.kind)
+            if keep:
+                acts.append(h.clone())
+        return (h, acts) if keep else h

@@ -138,6 +138,35 @@ def test_conv_and_im2col_errors(L):
     assert call(wb=need - 1) == WORKSPACE
 
 
+def test_packed_conv_errors(L):
+    cp = L.bnn_conv2d_packed
+    geo = (2, 128, 8, 8, 64, 3, 3, 1, 1, 1, 1)
+
+    def call(x=A16, w=A16, g=geo, pool=0, oi=None, of=None, op=A16, sc=A16, bi=A16):
+        return cp(x, w, *g, pool, oi, of, op, sc, bi, None)
+
+    assert call(pool=1) == SHAPE
+    assert call(g=(2, 128, 7, 7, 64, 3, 3, 1, 1, 1, 1), pool=2) == SHAPE  # odd output size cannot pool
+    assert call(g=(2, 128, 8, 8, -1, 3, 3, 1, 1, 1, 1)) == SHAPE
+    assert call(g=(0, 128, 8, 8, 64, 3, 3, 1, 1, 1, 1)) == OK
+    assert call(x=None) == NULL
+    assert call(op=None) == NULL  # no output at all
+    assert call(sc=None) == NULL  # packed output needs scale / bias
+    assert call(oi=A16) == UNSUPPORTED  # one kind of output per call
+    assert call(pool=2, op=None, oi=A16) == UNSUPPORTED  # pooling only in the packed epilogue
+    assert call(w=MIS) == ALIGN
+    fs = L.bnn_conv2d_f32_sign
+    assert fs(A16, A16, 2, 3, 8, 8, 128, 3, 3, 1, 1, 1, 1, None, A16, A16, None) == NULL
+    assert fs(A16, A16, 2, 4, 8, 8, 128, 3, 3, 1, 1, 1, 1, A16, A16, A16, None) == UNSUPPORTED  # 36 taps > 32
+    assert fs(A16, A16, 2, 3, 8, 8, 1000, 3, 3, 1, 1, 1, 1, A16, A16, A16, None) == UNSUPPORTED  # filter bank > LDS
+    assert fs(A16, A16, 2, 3, 8, 8, 128, 9, 9, 1, 1, 0, 0, A16, A16, A16, None) == SHAPE
+    pf = L.bnn_pack_fc_weight_nhwc
+    assert pf(A16, 10, 0, 4, 4, A16, None) == SHAPE
+    assert pf(None, 0, 64, 4, 4, None, None) == OK
+    assert pf(None, 10, 64, 4, 4, A16, None) == NULL
+    assert pf(A16, 10, 64, 4, 4, MIS, None) == ALIGN
+
+
 def test_glue_errors(L):
     mp = L.bnn_maxpool2x2
     assert mp(A16, 2, 4, 5, 6, A16, None, None, None, None) == SHAPE  # odd H

@@ -339,3 +339,109 @@ def test_prof_hook_records_kernels():
         assert B.prof_records() == []
     finally:
         B.prof_enable(False)
+
+
+# ---------------------------------------------------------------- packed activations between layers
+def _u64dev(a):
+    return dev(np.ascontiguousarray(a).view(np.int64))
+
+
+@pytest.mark.parametrize("case", [(2, 3, 10, 9, 128, 3, 3, 1, 1, 1, 1), (3, 3, 8, 8, 70, 3, 3, 2, 2, 1, 1),
+                                  (1, 1, 6, 6, 5, 5, 5, 1, 1, 2, 2), (2, 2, 7, 7, 200, 3, 3, 1, 1, 0, 0)])
+def test_conv2d_f32_sign_matches_oracle(case):
+    print(f"conv2d_f32_sign case={case}", flush=True)
+    N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
+    shape = inputs.ConvShape(*case)
+    d = inputs.conv_inputs(shape, seed=sum(case) + 1)
+    x = inputs.inject_specials(d["x"], 3, frac=0.01, with_nan=False)
+    got = as_u64(B.bnn_conv2d_f32_sign(dev(x), dev(d["w"]), dev(d["scale"]), dev(d["bias"]), (sH, sW), (pH, pW)))
+    ref = oracle.pack_nhwc(oracle.conv2d_f32_seq(x, d["w"], (sH, sW), (pH, pW), d["scale"], d["bias"]))
+    assert np.array_equal(got, ref)
+
+
+PACKED_CASES = CONV_CASES + [
+    (2, 128, 8, 8, 64, 3, 3, 1, 1, 1, 1),
+    (3, 128, 12, 10, 130, 3, 3, 1, 1, 1, 1),
+    (2, 256, 6, 6, 256, 3, 3, 1, 1, 1, 1),
+    (1, 64, 4, 6, 10, 3, 3, 1, 1, 1, 1),
+    (1, 320, 16, 16, 70, 3, 3, 1, 1, 1, 1),
+]
+
+
+@pytest.mark.parametrize("case", PACKED_CASES)
+def test_conv2d_packed_all_output_kinds(case):
+    print(f"conv2d_packed case={case}", flush=True)
+    N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
+    shape = inputs.ConvShape(*case)
+    d = inputs.conv_inputs(shape, seed=sum(case) + 2)
+    x = inputs.inject_specials(d["x"], 4, frac=0.01)
+    xp = _u64dev(oracle.pack_nhwc(x))
+    wp = B.bnn_pack_conv_weight(dev(d["w"]))
+    sc, bi = dev(d["scale"]), dev(d["bias"])
+    st, pd = (sH, sW), (pH, pW)
+    ref = oracle.conv2d_pm1(x, d["w"], st, pd)
+    assert np.array_equal(host(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, out="i32")), ref)
+    yref = oracle.scale_bias(ref, d["scale"], d["bias"], "nchw")
+    assert np.array_equal(host(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, scale=sc, bias=bi, out="f32")), yref)
+    got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, scale=sc, bias=bi, out="packed"))
+    assert np.array_equal(got, oracle.pack_nhwc(yref))
+    if shape.OH % 2 == 0 and shape.OW % 2 == 0:
+        pref = oracle.scale_bias(oracle.maxpool2x2_i32(ref), d["scale"], d["bias"], "nchw")
+        got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, pool=2, scale=sc, bias=bi, out="packed"))
+        assert np.array_equal(got, oracle.pack_nhwc(pref))
+
+
+def test_conv2d_packed_negative_scale_and_pool_order():
+    """With a negative scale the affine map is decreasing: pooling must act on the int32
+    accumulators before the affine map, not on its result."""
+    print("conv2d_packed negative scale", flush=True)
+    shape = inputs.ConvShape(2, 128, 8, 8, 64, 3, 3, 1, 1, 1, 1)
+    d = inputs.conv_inputs(shape, seed=77)
+    scale = -d["scale"]
+    xp = _u64dev(oracle.pack_nhwc(d["x"]))
+    wp = B.bnn_pack_conv_weight(dev(d["w"]))
+    ref = oracle.maxpool2x2_i32(oracle.conv2d_pm1(d["x"], d["w"], (1, 1), (1, 1)))
+    pref = oracle.pack_nhwc(oracle.scale_bias(ref, scale, d["bias"], "nchw"))
+    got = as_u64(B.bnn_conv2d_packed(xp, wp, 128, 64, 3, 3, (1, 1), (1, 1), pool=2, scale=dev(scale),
+                                     bias=dev(d["bias"]), out="packed"))
+    assert np.array_equal(got, pref)
+
+
+def test_pack_fc_weight_nhwc_matches_oracle():
+    print("pack_fc_weight_nhwc", flush=True)
+    rng = np.random.default_rng(41)
+    for (n_out, C, H, W) in [(10, 70, 2, 3), (33, 512, 4, 4), (4, 64, 1, 1)]:
+        w = rng.standard_normal((n_out, C * H * W)).astype(np.float32)
+        got = as_u64(B.bnn_pack_fc_weight_nhwc(dev(w), C, H, W))
+        assert np.array_equal(got, oracle.pack_fc_weight_nhwc(w, C, H, W))
+
+
+@pytest.mark.parametrize("reading", ["A", "B"])
+def test_cfg4_fused_stack_small_batch_every_layer(reading):
+    print(f"cfg4 fused stack batch 4 reading {reading}", flush=True)
+    from paper_1911_04477_amd.stack import VggStackFused
+    d = inputs.cfg4(batch=4, reading=reading)
+    net = VggStackFused(d["layers"], d["params"], batch=4, device=DEV)
+    out, acts = net.forward(dev(d["x"]), keep=True)
+    ref = oracle.vgg_stack(d["x"], d["layers"], d["params"])
+    for i, (L, g, r) in enumerate(zip(d["layers"], acts, ref["acts"])):
+        if L.kind in ("conv_f32", "bconv"):
+            assert np.array_equal(as_u64(g), oracle.pack_nhwc(r)), f"layer {i} ({L.kind})"
+        else:
+            assert np.array_equal(host(g), r), f"layer {i} ({L.kind})"
+    assert np.array_equal(host(out), ref["out"])
+
+
+def test_cfg4_fused_stack_full_batch_sampled_images():
+    print("cfg4 fused stack batch 256", flush=True)
+    from paper_1911_04477_amd.stack import VggStack, VggStackFused
+    d = inputs.cfg4(batch=256)
+    net = VggStackFused(d["layers"], d["params"], batch=256, device=DEV)
+    xd = dev(d["x"])
+    out = host(net.forward(xd))
+    pick = [0, 57, 255]
+    ref = oracle.vgg_stack(d["x"][pick], d["layers"], d["params"])
+    assert np.array_equal(out[pick], ref["out"])
+    # and the whole batch against the unfused path (independent kernels, same arithmetic)
+    out_unfused = host(VggStack(d["layers"], d["params"], batch=256, device=DEV).forward(xd))
+    assert np.array_equal(out, out_unfused)

@@ -388,3 +388,25 @@ def test_vgg_stack_shapes_and_batch_independence():
     r1 = oracle.vgg_stack(d["x"][1:2], d["layers"], d["params"])
     assert np.array_equal(r1["out"], r["out"][1:2])
     assert inputs.stack_bit_macs(d["layers"], 256) == 156_766_306_304
+
+
+def test_pack_nhwc_and_fc_weight_reorder_keep_the_product():
+    """Packing activations NHWC and re-ordering the FC weight the same way is a common
+    permutation of the reduction axis: Hamming distances must give back the NCHW-flattened GEMM."""
+    rng = np.random.default_rng(31)
+    N, C, H, W, n_out = 3, 70, 2, 3, 5
+    y = rng.standard_normal((N, C, H, W)).astype(np.float32)
+    w = rng.standard_normal((n_out, C * H * W)).astype(np.float32)
+    yp = oracle.pack_nhwc(y)
+    assert yp.shape == (N, H, W, 2)
+    # bit c of pixel (h, w) is the sign of y[n, c, h, w]; pad bits are 0
+    for n, c, h, ww in [(0, 0, 0, 0), (1, 63, 1, 2), (2, 64, 0, 1), (2, 69, 1, 0)]:
+        assert ((int(yp[n, h, ww, c // 64]) >> (c % 64)) & 1) == int(y[n, c, h, ww] >= 0)
+    assert np.all(yp[..., 1] >> np.uint64(6) == 0)
+    wp = oracle.pack_fc_weight_nhwc(w, C, H, W)
+    ref = oracle.gemm_pm1(y.reshape(N, -1), w)
+    rows = yp.reshape(N, -1)
+    for n in range(N):
+        for o in range(n_out):
+            ham = sum(bin(int(a) ^ int(b)).count("1") for a, b in zip(rows[n].tolist(), wp[o].tolist()))
+            assert ref[n, o] == C * H * W - 2 * ham
