@@ -178,8 +178,7 @@ bnn_status bnn_conv2d_packed(const uint64_t *x_packed, const uint64_t *w_packed,
  * bnn_conv2d_f32_sign -- real-valued first layer of the stack with binarized output:
  * bnn_conv2d_f32 (same fixed summation order) followed by fma(scale[d], acc, bias[d]) and
  * the sign, written as a packed NHWC image [N, OH, OW, ceil(D/64)].  Limited to
- * C*kH*kW <= 32 taps and D*(C*kH*kW rounded up to 4) + 2*D <= 16384 floats of filter data
- * (BNN_ERR_UNSUPPORTED otherwise).
+ * C*kH*kW <= 32 taps (BNN_ERR_UNSUPPORTED otherwise).
  */
 bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N, int C, int H, int W, int D,
                                int kH, int kW, int sH, int sW, int pH, int pW, const float *scale,

@@ -76,31 +76,27 @@ static bnn_status conv_limits(int N, int C, int H, int W, int D, int kH, int kW,
 }
 
 // ---- real-valued first layer with binarized, packed output ----------------------------------
-// One thread per output pixel.  The input patch (K = C*kH*kW <= 32 taps) sits in registers,
-// the filter bank, scale and bias in LDS (read with wave-uniform addresses, i.e. broadcast).
+// One thread per output pixel.  The input patch (K = C*kH*kW <= 32 taps) sits in registers.
+// The filter bank, scale and bias are wave-uniform, so they are read through the constant
+// address space with scalar loads and enter v_fma as the scalar operand (an LDS copy would
+// make the CU's single LDS pipe the bottleneck: four SIMDs reading 7 x 16 bytes per channel).
 // Every output channel is the sequential fma chain over (c, kh, kw), then fma(scale, acc,
 // bias); only its sign is kept, 64 channels per stored word.
 constexpr int F32S_KMAX = 32;
-__global__ __launch_bounds__(256) void conv2d_f32_sign_kernel(const float *__restrict__ x, const float *__restrict__ w,
-                                                              int C, int H, int W, int D, int kH, int kW, int sH,
-                                                              int sW, int pH, int pW, int OH, int OW,
-                                                              const float *__restrict__ scale,
-                                                              const float *__restrict__ bias,
-                                                              uint64_t *__restrict__ outp, int cw_out, FastDiv divOW,
-                                                              FastDiv divOH, uint32_t total_pix, int K, int Kp) {
-  extern __shared__ float smem[];
-  float *sWt = smem;              // [D][Kp], Kp = K rounded up to 4
-  float *sSc = smem + D * Kp;     // [D]
-  float *sBi = sSc + D;           // [D]
-  for (int idx = threadIdx.x; idx < D * Kp; idx += 256) {
-    const int d = idx / Kp, k = idx - d * Kp;
-    sWt[idx] = k < K ? w[(size_t)d * K + k] : 0.0f;
-  }
-  for (int d = threadIdx.x; d < D; d += 256) {
-    sSc[d] = scale[d];
-    sBi[d] = bias[d];
-  }
-  __syncthreads();
+#define BNN_CONST_AS __attribute__((address_space(4)))
+typedef const float BNN_CONST_AS *cf32_ptr;
+
+template <int KT>  // KT = K when known at compile time (27 for 3x3x3), else 0
+__global__ __launch_bounds__(256) void conv2d_f32_sign_kernel(const float *__restrict__ x, const float *w_, int C,
+                                                              int H, int W, int D, int kH, int kW, int sH, int sW,
+                                                              int pH, int pW, int OH, int OW, const float *scale_,
+                                                              const float *bias_, uint64_t *__restrict__ outp,
+                                                              int cw_out, FastDiv divOW, FastDiv divOH,
+                                                              uint32_t total_pix, int K_rt) {
+  const int K = KT > 0 ? KT : K_rt;
+  const cf32_ptr w = (cf32_ptr)(uintptr_t)w_;
+  const cf32_ptr scale = (cf32_ptr)(uintptr_t)scale_;
+  const cf32_ptr bias = (cf32_ptr)(uintptr_t)bias_;
   const uint32_t p = blockIdx.x * 256u + threadIdx.x;
   if (p >= total_pix) return;
   const uint32_t t = fdiv(p, divOW);
@@ -110,9 +106,10 @@ __global__ __launch_bounds__(256) void conv2d_f32_sign_kernel(const float *__res
   const int ih0 = (int)(oh * sH) - pH, iw0 = (int)(ow * sW) - pW;
   const float *xn = x + (size_t)n * C * H * W;
   const int taps = kH * kW;
-  float xv[F32S_KMAX];
+  constexpr int KU = KT > 0 ? KT : F32S_KMAX;
+  float xv[KU];
 #pragma unroll
-  for (int k = 0; k < F32S_KMAX; ++k) {
+  for (int k = 0; k < KU; ++k) {
     float v = 0.0f;
     if (k < K) {
       const int c = k / taps, r = k - c * taps;
@@ -125,20 +122,14 @@ __global__ __launch_bounds__(256) void conv2d_f32_sign_kernel(const float *__res
   for (int d0 = 0; d0 < D; d0 += 64) {
     uint32_t lo = 0, hi = 0;
     const int dn = D - d0 < 64 ? D - d0 : 64;
+#pragma unroll 4
     for (int dd = 0; dd < dn; ++dd) {
-      const float4 *wr = reinterpret_cast<const float4 *>(sWt + (size_t)(d0 + dd) * Kp);
+      const cf32_ptr wr = w + (size_t)(d0 + dd) * K;
       float acc = 0.0f;
 #pragma unroll
-      for (int k4 = 0; k4 < F32S_KMAX / 4; ++k4) {
-        if (4 * k4 < K) {
-          const float4 w4 = wr[k4];
-          acc = fmaf(xv[4 * k4], w4.x, acc);
-          if (4 * k4 + 1 < K) acc = fmaf(xv[4 * k4 + 1], w4.y, acc);
-          if (4 * k4 + 2 < K) acc = fmaf(xv[4 * k4 + 2], w4.z, acc);
-          if (4 * k4 + 3 < K) acc = fmaf(xv[4 * k4 + 3], w4.w, acc);
-        }
-      }
-      const uint32_t bit = fmaf(sSc[d0 + dd], acc, sBi[d0 + dd]) >= 0.0f ? 1u : 0u;
+      for (int k = 0; k < KU; ++k)
+        if (k < K) acc = fmaf(xv[k], wr[k], acc);
+      const uint32_t bit = fmaf(scale[d0 + dd], acc, bias[d0 + dd]) >= 0.0f ? 1u : 0u;
       if (dd < 32) lo |= bit << dd; else hi |= bit << (dd - 32);
     }
     outp[(size_t)p * cw_out + (d0 >> 6)] = ((uint64_t)hi << 32) | lo;
@@ -233,19 +224,22 @@ extern "C" bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N,
   if (!x || !w || !scale || !bias || !out_packed) return BNN_ERR_NULL;
   if (!aligned16(x) || !aligned16(w) || !aligned16(out_packed)) return BNN_ERR_ALIGN;
   const int64_t K = (int64_t)C * kH * kW;
-  const int64_t Kp = (K + 3) / 4 * 4;
-  const size_t lds = (size_t)(D * Kp + 2 * D) * sizeof(float);
-  if (K > F32S_KMAX || lds > 64 * 1024) return BNN_ERR_UNSUPPORTED;
+  if (K > F32S_KMAX) return BNN_ERR_UNSUPPORTED;
   const int64_t OH = bnn_conv_out_dim(H, kH, sH, pH), OW = bnn_conv_out_dim(W, kW, sW, pW);
   const int64_t total = (int64_t)N * OH * OW;
   if (total > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
   {
     ProfScope ps(KID_CONV_F32_SIGN, s);
-    hipLaunchKernelGGL(conv2d_f32_sign_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), lds, s, x, w, C, H, W,
-                       D, kH, kW, sH, sW, pH, pW, (int)OH, (int)OW, scale, bias, out_packed,
-                       (int)bnn_packed_words(D), FastDiv((uint32_t)OW), FastDiv((uint32_t)OH), (uint32_t)total, (int)K,
-                       (int)Kp);
+    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    if (K == 27)
+      hipLaunchKernelGGL(conv2d_f32_sign_kernel<27>, grid, block, 0, s, x, w, C, H, W, D, kH, kW, sH, sW, pH, pW,
+                         (int)OH, (int)OW, scale, bias, out_packed, (int)bnn_packed_words(D), FastDiv((uint32_t)OW),
+                         FastDiv((uint32_t)OH), (uint32_t)total, (int)K);
+    else
+      hipLaunchKernelGGL(conv2d_f32_sign_kernel<0>, grid, block, 0, s, x, w, C, H, W, D, kH, kW, sH, sW, pH, pW,
+                         (int)OH, (int)OW, scale, bias, out_packed, (int)bnn_packed_words(D), FastDiv((uint32_t)OW),
+                         FastDiv((uint32_t)OH), (uint32_t)total, (int)K);
   }
   return launch_status();
 }

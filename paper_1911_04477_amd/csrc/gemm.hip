@@ -193,6 +193,18 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   u32x4 stage[PPT];
   auto stage_load = [&](int s) {
     const int wbase = stage_word0(s);
+    int tap_cw[2] = {0, 0}, tap_kh[2] = {0, 0}, tap_kw[2] = {0, 0};
+    if constexpr (BMODE == 1) {
+#pragma unroll
+      for (int qq = 0; qq < 2; ++qq) {
+        const uint32_t w = (uint32_t)__builtin_amdgcn_readfirstlane(wbase + 2 * qq);
+        const uint32_t tap = fdiv(w, p.g.divCw);
+        tap_cw[qq] = (int)(w - tap * (uint32_t)p.g.Cw);
+        const uint32_t kh = fdiv(tap, p.g.divKW);
+        tap_kh[qq] = (int)kh;
+        tap_kw[qq] = (int)(tap - kh * (uint32_t)p.g.kW);
+      }
+    }
 #pragma unroll
     for (int t = 0; t < PPT; ++t) {
       const int idx = t * Cfg::THREADS + tid;
@@ -217,12 +229,12 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
       } else {
         if (s_ok[t] && w0 <= last_w) {
           if (!(p.g.Cw & 1) && !(wbase & 1)) {
-            // both words of the piece belong to one tap: one 16-byte load
-            const uint32_t tap = fdiv((uint32_t)w0, p.g.divCw);
-            const int cw = w0 - (int)tap * p.g.Cw;
-            const uint32_t kh = fdiv(tap, p.g.divKW);
-            const int kw = (int)(tap - kh * p.g.kW);
-            const int ih = s_ih0[t] + (int)kh, iw = s_iw0[t] + kw;
+            // both words of the piece belong to one tap: one 16-byte load.  The tap of each of
+            // the two pieces of a chunk is wave-uniform (decoded once per chunk on the scalar
+            // unit, see tap_* below); a lane only selects by its piece index q.
+            const int cw = q ? tap_cw[1] : tap_cw[0];
+            const int ih = s_ih0[t] + (q ? tap_kh[1] : tap_kh[0]);
+            const int iw = s_iw0[t] + (q ? tap_kw[1] : tap_kw[0]);
             if (ih >= 0 && ih < p.g.H && iw >= 0 && iw < p.g.W) {
               v = *reinterpret_cast<const u32x4 *>(
                   p.g.act + ((size_t)s_pix0[t] + (size_t)(ih * p.g.W + iw)) * p.g.Cw + cw);
@@ -509,7 +521,7 @@ bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s) {
     case 0: return launch_cfg<8, 4, 1, 2>(p, bmode, emode, s, KID_XNOR_GEMM);        // 32 x 512
     case 1: return launch_cfg<4, 4, 1, 4>(p, bmode, emode, s, KID_XNOR_GEMM);        // 32 x 256
     case 2: return launch_cfg<1, 4, 1, 4>(p, bmode, emode, s, KID_XNOR_GEMM_SMALL);  // 32 x 64
-    case 3: return launch_cfg<4, 8, 1, 4>(p, bmode, emode, s, KID_XNOR_GEMM);        // 64 x 256
+    case 3: return launch_cfg<4, 8, 1, 6>(p, bmode, emode, s, KID_XNOR_GEMM);        // 64 x 256
     case 4: return launch_cfg<2, 4, 1, 4>(p, bmode, emode, s, KID_XNOR_GEMM);        // 32 x 128
     case 6: return launch_cfg<2, 8, 1, 4>(p, bmode, emode, s, KID_XNOR_GEMM);        // 64 x 128
     default: return BNN_ERR_UNSUPPORTED;

@@ -158,7 +158,6 @@ def test_packed_conv_errors(L):
     fs = L.bnn_conv2d_f32_sign
     assert fs(A16, A16, 2, 3, 8, 8, 128, 3, 3, 1, 1, 1, 1, None, A16, A16, None) == NULL
     assert fs(A16, A16, 2, 4, 8, 8, 128, 3, 3, 1, 1, 1, 1, A16, A16, A16, None) == UNSUPPORTED  # 36 taps > 32
-    assert fs(A16, A16, 2, 3, 8, 8, 1000, 3, 3, 1, 1, 1, 1, A16, A16, A16, None) == UNSUPPORTED  # filter bank > LDS
     assert fs(A16, A16, 2, 3, 8, 8, 128, 9, 9, 1, 1, 0, 0, A16, A16, A16, None) == SHAPE
     pf = L.bnn_pack_fc_weight_nhwc
     assert pf(A16, 10, 0, 4, 4, A16, None) == SHAPE
