@@ -233,6 +233,29 @@ def side_measurements():
     return res
 
 
+def mfma_ablation():
+    """The int8-MFMA-on-0/1 ablation beside the VALU GEMM on the GEMM view of cfg 5a and cfg 3."""
+    import torch
+    from paper_1911_04477_amd import binding as B
+    dev = "cuda:0"
+    out = {}
+    for name, (M, N, K) in (("cfg5a_gemm_256x200704x2304", (256, 200704, 2304)),
+                            ("cfg3_gemm_128x131072x1152", (128, 131072, 1152))):
+        Kw = (K + 63) // 64
+        A = torch.randint(-2**62, 2**62, (M, Kw), dtype=torch.int64, device=dev)
+        Bm = torch.randint(-2**62, 2**62, (N, Kw), dtype=torch.int64, device=dev)
+        C = torch.empty((M, N), dtype=torch.int32, device=dev)
+        C2 = torch.empty((M, N), dtype=torch.int32, device=dev)
+        tv, _ = time_steps(lambda: B.bnn_xnor_gemm(A, Bm, K, C), 20, 5)
+        tm, _ = time_steps(lambda: B.bnn_xnor_gemm_mfma_i8(A, Bm, K, C2), 20, 5)
+        bops = 2.0 * M * N * K
+        out[name] = {"valu_TBOPS": round(bops / (tv / 20) / 1e12, 1), "mfma_i8_TBOPS": round(bops / (tm / 20) / 1e12, 1),
+                     "bit_identical": bool((C == C2).all().item()),
+                     "mfma_i8_frac_of_int8_dense_peak": round(bops / (tm / 20) / 5.0e15, 4)}
+        del A, Bm, C, C2
+    return out
+
+
 def other_configs(args):
     out = {}
     for name in ("cfg2", "cfg3", "cfg5a", "cfg5b"):
@@ -302,6 +325,7 @@ def main():
         line["streaming"] = side_measurements()
         line["hbm_peak_GBs"] = HBM_PEAK_GBS
         line["other_configs"] = other_configs(args)
+        line["mfma_ablation"] = mfma_ablation()
     print(json.dumps(line), flush=True)
 
 

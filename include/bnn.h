@@ -225,6 +225,19 @@ bnn_status bnn_conv2d_f32(const float *x, const float *w, int N, int C, int H, i
 bnn_status bnn_fc_f32(const float *x, const float *w, const float *bias, int64_t M, int64_t K,
                       int64_t N, int sign_input, float *out, void *stream);
 
+/* ---- ablation --------------------------------------------------------------------------- */
+
+/*
+ * bnn_xnor_gemm_mfma_i8 -- ABLATION of bnn_xnor_gemm, same arguments and bit-identical
+ * result, computed on the matrix cores: CDNA4 has no 1-bit MFMA, so every packed bit is
+ * expanded on the fly to an int8 (0 / 1) and V_MFMA_I32_32X32X32_I8 counts the positions
+ * where both operands are +1; K - 2*popcount(a XOR b) follows from that count and the two
+ * rows' own +1 counts.  Measured beside the VALU path, not used by any other entry point.
+ */
+bnn_status bnn_xnor_gemm_mfma_i8(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb,
+                                 int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K,
+                                 void *stream);
+
 /* ---- measurement helpers ------------------------------------------------------------ */
 
 /*

@@ -21,7 +21,8 @@ enum KernelId : int {
   KID_COPY_PROBE = 9,
   KID_XNOR_GEMM_SMALL = 10,
   KID_CONV_F32_SIGN = 11,
-  KID_COUNT = 12
+  KID_XNOR_GEMM_MFMA = 12,
+  KID_COUNT = 13
 };
 
 // Timing hook: records an event pair around a launch when profiling is on.

@@ -445,3 +445,25 @@ def test_cfg4_fused_stack_full_batch_sampled_images():
     # and the whole batch against the unfused path (independent kernels, same arithmetic)
     out_unfused = host(VggStack(d["layers"], d["params"], batch=256, device=DEV).forward(xd))
     assert np.array_equal(out, out_unfused)
+
+
+# ---------------------------------------------------------------- MFMA ablation
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (37, 150, 300), (128, 128, 64), (130, 257, 1152), (64, 64, 256),
+                                   (200, 333, 2304 + 17), (5, 700, 63)])
+def test_mfma_ablation_matches_oracle(M, N, K):
+    print(f"mfma M={M} N={N} K={K}", flush=True)
+    rng = np.random.default_rng(M * 7919 + N * 31 + K)
+    A = inputs.inject_specials(rng.standard_normal((M, K)).astype(np.float32), 1, frac=0.002)
+    Bm = inputs.inject_specials(rng.standard_normal((N, K)).astype(np.float32), 2, frac=0.002)
+    Ap, Bp = B.bnn_encode(dev(A)), B.bnn_encode(dev(Bm))
+    got = host(B.bnn_xnor_gemm_mfma_i8(Ap, Bp, K))
+    assert np.array_equal(got, oracle.gemm_pm1(A, Bm))
+
+
+def test_mfma_ablation_equals_valu_path_at_cfg2():
+    print("mfma cfg2", flush=True)
+    d = inputs.cfg2()
+    Ap, Wp = B.bnn_encode(dev(d["act"])), B.bnn_encode(dev(d["wt"]))
+    a = host(B.bnn_xnor_gemm_mfma_i8(Ap, Wp, inputs.CFG2.K))
+    b = host(B.bnn_xnor_gemm(Ap, Wp, inputs.CFG2.K))
+    assert np.array_equal(a, b)
