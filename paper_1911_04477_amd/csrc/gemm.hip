@@ -98,7 +98,8 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   constexpr int RS = Cfg::RS;
   constexpr int PPT = Cfg::PPT;
   constexpr int QPR = KC / 4;  // 16-byte pieces per row
-  static_assert(EMODE == 0 || (WM == 8 && WN == 1 && TN == 4), "packed epilogue needs the 64 x 256 tile");
+  static_assert(EMODE == 0 || ((WM == 8 || WM == 4) && WN == 1 && (TN == 4 || TN == 2)),
+                "packed epilogue needs 64- or 32-row tiles");
   __shared__ __attribute__((aligned(16))) uint32_t sB[2 * Cfg::TILE];
 
   const int tid = threadIdx.x;
@@ -139,13 +140,15 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
 #pragma unroll
     for (int j = 0; j < TN; ++j) acc[i][j] = 0;
 
-  // K bookkeeping (all wave-uniform).  Full chunks cover words [0, 4*nfull).  When bits
-  // remain and the row has at least 4 words, a last "window" chunk covers words
-  // [Kw64-4, Kw64); otherwise (K < 193 bits) the remainder is done one dword at a time.
+  // K bookkeeping (all wave-uniform).  Full chunks cover words [0, 4*nfull).  Two words left
+  // over are done by a half chunk; one or three by a last "window" chunk over words
+  // [Kw64-4, Kw64) when the row has at least 4 words; else one dword at a time.
   const int nfull = p.Kbits / (32 * KC);
   const int rem_bits = p.Kbits - nfull * 32 * KC;
-  const bool window = rem_bits > 0 && p.Kw64 >= 4;
-  const bool slow_tail = rem_bits > 0 && !window;
+  const int r_words = p.Kw64 - 4 * nfull;                           // words past the full chunks: 0..3
+  const bool half = r_words == 2;                                   // finished by one half chunk (4 dwords)
+  const bool window = rem_bits > 0 && !half && p.Kw64 >= 4;         // finished by an overlapping chunk
+  const bool slow_tail = rem_bits > 0 && !half && !window;          // rows of 1 or 3 words only
   const int nstages = nfull + (rem_bits > 0 ? 1 : 0);
   const int last_w = p.Kw64 - 1;
   const int tail_bits = p.Kbits & 63;
@@ -343,7 +346,45 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
     }
   }
 
-  // ---- rows shorter than four words (K < 193): one dword at a time --------------------------
+  // ---- half chunk: the last two words of rows of 4*n + 2 words -------------------------------
+  if (half) {
+    const uint32_t *sBl = &sB[(nfull & 1) * Cfg::TILE + lane_row];
+    const uint64_t Abase = Abase0 + (uint64_t)(uint32_t)(4 * nfull) * 8u;
+    u32x4 a[TM];
+    u32x4 b[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      asm volatile("s_load_dwordx4 %0, %1, %2" : "=s"(a[i]) : "s"(Abase), "s"(aoffb[i]));
+#pragma unroll
+    for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&sBl[j * 64 * RS]);
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+s"(a[0]), "+s"(a[1]), "+s"(a[2]), "+s"(a[3]), "+s"(a[4]), "+s"(a[5]), "+s"(a[6]), "+s"(a[7]));
+    const uint32_t m2 = (uint32_t)tail_mask, m3 = (uint32_t)(tail_mask >> 32);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      a[i][2] &= m2;
+      a[i][3] &= m3;
+    }
+    uint32_t t0, t1;
+#define BNN_BV(j, d) b[j][d]
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      if constexpr (YIELD) {
+        if constexpr (TN == 8) BNN_GEMM_HALF_8(acc[i], a[i], BNN_BV, t0, t1);
+        else if constexpr (TN == 4) BNN_GEMM_HALF_4(acc[i], a[i], BNN_BV, t0, t1);
+        else if constexpr (TN == 2) BNN_GEMM_HALF_2(acc[i], a[i], BNN_BV, t0, t1);
+        else BNN_GEMM_HALF_1(acc[i], a[i], BNN_BV, t0, t1);
+      } else {
+        if constexpr (TN == 8) BNN_GEMM_HALF_8_NY(acc[i], a[i], BNN_BV, t0, t1);
+        else if constexpr (TN == 4) BNN_GEMM_HALF_4_NY(acc[i], a[i], BNN_BV, t0, t1);
+        else if constexpr (TN == 2) BNN_GEMM_HALF_2_NY(acc[i], a[i], BNN_BV, t0, t1);
+        else BNN_GEMM_HALF_1_NY(acc[i], a[i], BNN_BV, t0, t1);
+      }
+    }
+#undef BNN_BV
+  }
+
+  // ---- rows of one or three words (K < 193): one dword at a time ----------------------------
   // B is already masked / zero-filled by the staging; A is masked here.
   if (slow_tail) {
     const uint32_t *sBl = &sB[(nfull & 1) * Cfg::TILE + lane_row];
@@ -416,10 +457,10 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
       }
     }
   } else {
-    // Binarizing epilogue.  Row m is output channel m; the workgroup's 64 rows are exactly
-    // one 64-bit channel word (word index mi) of every pixel in its tile.  Each lane turns
-    // its 8 channels into a byte per output pixel, the 8 waves' bytes meet in LDS, and one
-    // thread per pixel writes the assembled word.
+    // Binarizing epilogue.  Row m is output channel m; the workgroup's 8 * WM rows are one
+    // 64-bit channel word (WM = 8), or one 32-bit half of it (WM = 4), of every pixel in its
+    // tile.  Each lane turns its 8 channels into a byte per output pixel, the waves' bytes
+    // meet in LDS, and one thread per pixel writes the assembled (half) word.
     const int pool = kp->g.pool;
     uint64_t *const outp = kp->outp;
     const int cw_out = kp->cw_out;
@@ -448,19 +489,29 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
     __syncthreads();  // every wave is done reading the B tiles: LDS is reused for the output bytes
     uint8_t *sO = reinterpret_cast<uint8_t *>(sB);
     if (pool) {
-      sO[lane * 8 + wm] = (uint8_t)bytes[0];
+      sO[lane * WM + wm] = (uint8_t)bytes[0];
     } else {
 #pragma unroll
-      for (int j = 0; j < TN; ++j) sO[(j * 64 + lane) * 8 + wm] = (uint8_t)bytes[j];
+      for (int j = 0; j < TN; ++j) sO[(j * 64 + lane) * WM + wm] = (uint8_t)bytes[j];
     }
     __syncthreads();
-    const int npix = pool ? 64 : 256;
+    const int npix = pool ? 64 : 64 * TN;
     if (tid < npix) {
-      const uint2 w = *reinterpret_cast<const uint2 *>(&sO[tid * 8]);
       // global pixel index: pooled window index, or column index (NHWC pixel order)
       const int64_t gp = pool ? (int64_t)ni * 64 + tid : (int64_t)n0 + tid;
       const int64_t limit = pool ? (int64_t)(N >> 2) : (int64_t)N;
-      if (gp < limit) *reinterpret_cast<uint2 *>(outp + gp * cw_out + mi) = w;
+      if (gp < limit) {
+        if constexpr (WM == 8) {
+          const uint2 w = *reinterpret_cast<const uint2 *>(&sO[tid * 8]);
+          *reinterpret_cast<uint2 *>(outp + gp * cw_out + mi) = w;
+        } else {
+          // 32 channels: half of word (mi / 2); a last odd half past D is written as zeros
+          const uint32_t w = *reinterpret_cast<const uint32_t *>(&sO[tid * 4]);
+          uint32_t *o32 = reinterpret_cast<uint32_t *>(outp) + (gp * cw_out) * 2;
+          o32[mi] = w;
+          if (mi == kp->tilesM - 1 && (kp->tilesM & 1)) o32[mi + 1] = 0u;  // channels past D: pad bits 0
+        }
+      }
     }
   }
 }
@@ -486,9 +537,9 @@ static bnn_status launch_cfg(GemmParams &p, int bmode, int emode, hipStream_t s,
   // share a SIMD; with fewer they cost issue slots.  256 CUs x 4 SIMDs.
   const int64_t waves = blocks * (Cfg::THREADS / 64);
   const bool yield = waves >= 2 * 1024;
-  if constexpr (TN == 4 && WM == 8 && WN == 1) {
+  if constexpr ((TN == 4 || TN == 2) && (WM == 8 || WM == 4) && WN == 1) {
     if (emode == 1) {
-      if (bmode != 1) return BNN_ERR_UNSUPPORTED;
+      if (bmode != 1 || (p.g.pool && TN != 4)) return BNN_ERR_UNSUPPORTED;
       return yield ? launch_one<TN, WM, WN, MINW, 1, 1, 1>(p, s, kid) : launch_one<TN, WM, WN, MINW, 1, 1, 0>(p, s, kid);
     }
   }
@@ -506,7 +557,15 @@ int g_force_cfg = -1;  // test / tuning hook: -1 = heuristic
 
 bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s) {
   int cfg = g_force_cfg;
-  if (emode == 1) cfg = 3;                      // the packed epilogue is written for the 64 x 256 tile
+  if (emode == 1) {
+    // tiles the packed epilogue is written for: 64 x 256 (3), 64 x 128 (6), 32 x 256 (1), 32 x 128 (4);
+    // pooling needs four columns per lane (3 or 1)
+    const bool ok = p.g.pool ? (cfg == 3 || cfg == 1) : (cfg == 3 || cfg == 6 || cfg == 1 || cfg == 4);
+    if (!ok) {
+      const int64_t t256e = (int64_t)((p.M + 63) / 64) * ((p.N + 255) / 256);
+      cfg = t256e >= 768 ? 3 : 1;
+    }
+  }
   if (bmode == 1 && (cfg == 0)) cfg = 3;        // no implicit-GEMM instantiation of the 32 x 512 tile
   if (cfg < 0) {
     // Measured on MI355X: 64 x 256 (TN = 4, eight waves per workgroup, six per SIMD) is the

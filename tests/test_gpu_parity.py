@@ -368,6 +368,33 @@ PACKED_CASES = CONV_CASES + [
 ]
 
 
+@pytest.mark.parametrize("cfg", [1, 3, 4, 6])
+@pytest.mark.parametrize("case", PACKED_CASES[-5:] + PACKED_CASES[1:4])
+def test_conv2d_packed_forced_tiles(case, cfg):
+    """The binarizing epilogue on every tile shape it is written for (the pooled form only
+    exists for the four-column tiles; other requests fall back to a legal tile)."""
+    print(f"conv2d_packed forced cfg={cfg} case={case}", flush=True)
+    N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
+    shape = inputs.ConvShape(*case)
+    d = inputs.conv_inputs(shape, seed=sum(case) + 3)
+    xp = _u64dev(oracle.pack_nhwc(d["x"]))
+    wp = B.bnn_pack_conv_weight(dev(d["w"]))
+    sc, bi = dev(d["scale"]), dev(d["bias"])
+    st, pd = (sH, sW), (pH, pW)
+    ref = oracle.conv2d_pm1(d["x"], d["w"], st, pd)
+    B.lib().bnn_internal_force_gemm_cfg(cfg)
+    try:
+        got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, scale=sc, bias=bi, out="packed"))
+        assert np.array_equal(got, oracle.pack_nhwc(oracle.scale_bias(ref, d["scale"], d["bias"], "nchw")))
+        if shape.OH % 2 == 0 and shape.OW % 2 == 0:
+            pref = oracle.scale_bias(oracle.maxpool2x2_i32(ref), d["scale"], d["bias"], "nchw")
+            got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, pool=2, scale=sc, bias=bi, out="packed"))
+            assert np.array_equal(got, oracle.pack_nhwc(pref))
+        assert np.array_equal(host(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, out="i32")), ref)
+    finally:
+        B.lib().bnn_internal_force_gemm_cfg(-1)
+
+
 @pytest.mark.parametrize("case", PACKED_CASES)
 def test_conv2d_packed_all_output_kinds(case):
     print(f"conv2d_packed case={case}", flush=True)
