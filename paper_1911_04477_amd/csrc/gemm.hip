@@ -92,6 +92,57 @@ __device__ __forceinline__ void decode_col(const ConvGeom &g, uint32_t n, uint32
   }
 }
 
+// Store of an 8 x TN accumulator tile: K - 2*acc as int32 and / or fma(scale, acc, bias) as
+// fp32, row-major or scattered to NCHW.  The store-only parameters are read from the
+// kernel-argument segment through a pointer the optimizer cannot see through, so that they
+// occupy no SGPRs (or spill slots) during the main loop.
+template <int TN>
+__device__ __forceinline__ void store_tile(const int (&acc)[TM][TN], int m0, int nbase) {
+  const GemmParams BNN_CONST_AS *kp = (const GemmParams BNN_CONST_AS *)__builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(kp));
+  const int M = kp->M, N = kp->N, Kformula = kp->Kformula;
+  const float *const scale = kp->scale, *const bias = kp->bias;
+  const int axis = kp->axis;
+  int32_t *const Cp = kp->C;
+  float *const Yp = kp->Y;
+  const int64_t ldc = kp->ldc, ldy = kp->ldy, img_stride = kp->img_stride;
+  const uint32_t OHW = kp->OHW;
+  FastDiv divOHW;
+  divOHW.d = kp->divOHW.d; divOHW.mul = kp->divOHW.mul; divOHW.shift = kp->divOHW.shift;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = nbase + j * 64;
+    if (n >= N) continue;
+    const uint32_t img = fdiv((uint32_t)n, divOHW);
+    const uint32_t pix = (uint32_t)n - img * OHW;
+    const int64_t coff = (int64_t)img * img_stride + pix + (int64_t)m0 * ldc;
+    const int64_t yoff = (int64_t)img * img_stride + pix + (int64_t)m0 * ldy;
+    int32_t *cp = Cp ? Cp + coff : nullptr;
+    float *yp = Yp ? Yp + yoff : nullptr;
+    float sc = 1.0f, bi = 0.0f;
+    if (Yp && axis == BNN_CH_COL) {
+      sc = scale[n];
+      bi = bias[n];
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      if (m0 + i < M) {
+        const int v = Kformula - 2 * acc[i][j];
+        if (cp) *cp = v;
+        if (yp) {
+          if (axis == BNN_CH_ROW) {
+            sc = scale[m0 + i];
+            bi = bias[m0 + i];
+          }
+          *yp = fmaf(sc, (float)v, bi);
+        }
+      }
+      if (cp) cp += ldc;
+      if (yp) yp += ldy;
+    }
+  }
+}
+
 template <int TN, int WM, int WN, int MINW, int BMODE, int EMODE, int YIELD>
 __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParams p) {
   using Cfg = GemmCfg<TN, WM, WN>;
@@ -406,61 +457,17 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   }
 
   // ---- store ------------------------------------------------------------------------
-  // The store-only parameters are re-read from the kernel-argument segment here, through a
-  // pointer the optimizer cannot see through, so that they do not occupy SGPRs (or spill
-  // slots) during the main loop.
-  const GemmParams BNN_CONST_AS *kp = (const GemmParams BNN_CONST_AS *)__builtin_amdgcn_kernarg_segment_ptr();
-  asm volatile("" : "+s"(kp));
-  const int M = kp->M, N = kp->N, Kformula = kp->Kformula;
-  const float *const scale = kp->scale, *const bias = kp->bias;
-
   if constexpr (EMODE == 0) {
-    const int axis = kp->axis;
-    int32_t *const Cp = kp->C;
-    float *const Yp = kp->Y;
-    const int64_t ldc = kp->ldc, ldy = kp->ldy, img_stride = kp->img_stride;
-    const uint32_t OHW = kp->OHW;
-    FastDiv divOHW;
-    divOHW.d = kp->divOHW.d; divOHW.mul = kp->divOHW.mul; divOHW.shift = kp->divOHW.shift;
-
-    const int nbase = n0 + wn * 64 * TN + lane;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = nbase + j * 64;
-      if (n >= N) continue;
-      const uint32_t img = fdiv((uint32_t)n, divOHW);
-      const uint32_t pix = (uint32_t)n - img * OHW;
-      const int64_t coff = (int64_t)img * img_stride + pix + (int64_t)m0 * ldc;
-      const int64_t yoff = (int64_t)img * img_stride + pix + (int64_t)m0 * ldy;
-      int32_t *cp = Cp ? Cp + coff : nullptr;
-      float *yp = Yp ? Yp + yoff : nullptr;
-      float sc = 1.0f, bi = 0.0f;
-      if (Yp && axis == BNN_CH_COL) {
-        sc = scale[n];
-        bi = bias[n];
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        if (m0 + i < M) {
-          const int v = Kformula - 2 * acc[i][j];
-          if (cp) *cp = v;
-          if (yp) {
-            if (axis == BNN_CH_ROW) {
-              sc = scale[m0 + i];
-              bi = bias[m0 + i];
-            }
-            *yp = fmaf(sc, (float)v, bi);
-          }
-        }
-        if (cp) cp += ldc;
-        if (yp) yp += ldy;
-      }
-    }
+    store_tile<TN>(acc, m0, n0 + wn * 64 * TN + lane);
   } else {
     // Binarizing epilogue.  Row m is output channel m; the workgroup's 8 * WM rows are one
     // 64-bit channel word (WM = 8), or one 32-bit half of it (WM = 4), of every pixel in its
     // tile.  Each lane turns its 8 channels into a byte per output pixel, the waves' bytes
     // meet in LDS, and one thread per pixel writes the assembled (half) word.
+    const GemmParams BNN_CONST_AS *kp = (const GemmParams BNN_CONST_AS *)__builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(kp));
+    const int M = kp->M, N = kp->N, Kformula = kp->Kformula;
+    const float *const scale = kp->scale, *const bias = kp->bias;
     const int pool = kp->g.pool;
     uint64_t *const outp = kp->outp;
     const int cw_out = kp->cw_out;
@@ -516,6 +523,132 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   }
 }
 
+
+// ---- small problems: one independent wave per 8 x (64*TN) tile, no LDS, no barrier -------------
+// When a problem has too few tiles to put two waves on every SIMD, the LDS-staged kernel is
+// bound by its per-chunk latency chain (global load -> LDS -> barrier).  Here every lane reads
+// its own columns' words straight from global memory into registers, DEPTH chunks ahead, and
+// the wave never synchronises with anyone.  A is fetched with scalar loads as above.
+template <int TN, int DEPTH, int YIELD>
+__global__ __launch_bounds__(256) void xnor_gemm_direct_kernel(GemmParams p) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const uint32_t wid = blockIdx.x * 4u + (uint32_t)wave;  // tile index, M fastest
+  const int mi = (int)(wid % (uint32_t)p.tilesM);
+  const int ni = (int)(wid / (uint32_t)p.tilesM);
+  if (ni >= p.tilesN) return;
+  const int m0 = mi * TM;
+  const int nbase = ni * 64 * TN + lane;
+
+  uint32_t aoffb[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    int m = m0 + i;
+    m = m < p.M ? m : p.M - 1;
+    aoffb[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)m * (uint32_t)p.lda32 * 4u));
+  }
+  const uint32_t Abase_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)p.A);
+  const uint32_t Abase_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uintptr_t)p.A >> 32));
+  const uint64_t Abase0 = ((uint64_t)Abase_hi << 32) | (uint64_t)Abase_lo;
+  const cu32_ptr Ac = (cu32_ptr)(uintptr_t)p.A;
+
+  // this lane's TN rows of B (clamped: columns past N recompute column N-1 and are not stored)
+  const uint64_t *brow[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    int n = nbase + j * 64;
+    n = n < p.N ? n : p.N - 1;
+    brow[j] = p.B + (int64_t)n * p.ldb;
+  }
+
+  int acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = 0;
+
+  const int nfull = p.Kbits / (32 * KC);
+  auto load_b = [&](u32x8 (&b)[TN], int c) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const uint64_t *src = brow[j] + 4 * c;
+      if (p.b_vec16) {
+        b[j].lo = *reinterpret_cast<const u32x4 *>(src);
+        b[j].hi = *reinterpret_cast<const u32x4 *>(src + 2);
+      } else {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const uint2 v = *reinterpret_cast<const uint2 *>(src + w);
+          b[j][2 * w] = v.x;
+          b[j][2 * w + 1] = v.y;
+        }
+      }
+    }
+  };
+  auto compute = [&](u32x8 (&b)[TN], int c) {
+    const uint64_t Abase = Abase0 + (uint64_t)(uint32_t)c * 32u;
+    u32x8 a[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      asm volatile("s_load_dwordx8 %0, %1, %2" : "=s"(a[i]) : "s"(Abase), "s"(aoffb[i]));
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+s"(a[0]), "+s"(a[1]), "+s"(a[2]), "+s"(a[3]), "+s"(a[4]), "+s"(a[5]), "+s"(a[6]), "+s"(a[7]));
+    uint32_t t0, t1;
+#define BNN_BV(j, d) b[j][d]
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      if constexpr (YIELD) {
+        if constexpr (TN == 2) BNN_GEMM_ROW_2(acc[i], a[i], BNN_BV, t0, t1);
+        else BNN_GEMM_ROW_1(acc[i], a[i], BNN_BV, t0, t1);
+      } else {
+        if constexpr (TN == 2) BNN_GEMM_ROW_2_NY(acc[i], a[i], BNN_BV, t0, t1);
+        else BNN_GEMM_ROW_1_NY(acc[i], a[i], BNN_BV, t0, t1);
+      }
+    }
+#undef BNN_BV
+  };
+
+  // software pipeline over full chunks, DEPTH loads in flight (slots indexed statically)
+  u32x8 bq[DEPTH][TN];
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d)
+    if (d < nfull) load_b(bq[d], d);
+  int c = 0;
+  for (; c + DEPTH <= nfull; c += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      compute(bq[d], c + d);
+      if (c + d + DEPTH < nfull) load_b(bq[d], c + d + DEPTH);
+    }
+  }
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d)
+    if (c + d < nfull) compute(bq[d], c + d);
+
+  // bits past the last full chunk: one dword at a time, both operands masked
+  {
+    const int kd0 = nfull * KC;
+    const int tb32 = p.Kbits & 31;
+    const uint32_t *b32[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) b32[j] = reinterpret_cast<const uint32_t *>(brow[j]);
+#pragma unroll 1
+    for (int kd = kd0; kd < p.Kd; ++kd) {
+      const uint32_t mask = (kd == p.Kd - 1 && tb32) ? ((1u << tb32) - 1u) : 0xffffffffu;
+      uint32_t b[TN];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) b[j] = b32[j][kd] & mask;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const uint32_t a = Ac[(aoffb[i] >> 2) + kd] & mask;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = popc_acc(a ^ b[j], acc[i][j]);
+      }
+    }
+  }
+  store_tile<TN>(acc, m0, nbase);
+}
+
 // ---- host side ----------------------------------------------------------------------
 template <int TN, int WM, int WN, int MINW, int BMODE, int EMODE, int YIELD>
 static bnn_status launch_one(GemmParams &p, hipStream_t s, int kid) {
@@ -544,29 +677,44 @@ static bnn_status launch_cfg(GemmParams &p, int bmode, int emode, hipStream_t s,
     }
   }
   if (emode != 0) return BNN_ERR_UNSUPPORTED;
-  if (bmode == 1) {
-    if constexpr (TN == 8)
-      return BNN_ERR_UNSUPPORTED;
-    else
-      return yield ? launch_one<TN, WM, WN, MINW, 1, 0, 1>(p, s, kid) : launch_one<TN, WM, WN, MINW, 1, 0, 0>(p, s, kid);
-  }
+  if (bmode == 1)
+    return yield ? launch_one<TN, WM, WN, MINW, 1, 0, 1>(p, s, kid) : launch_one<TN, WM, WN, MINW, 1, 0, 0>(p, s, kid);
   return yield ? launch_one<TN, WM, WN, MINW, 0, 0, 1>(p, s, kid) : launch_one<TN, WM, WN, MINW, 0, 0, 0>(p, s, kid);
 }
 
 int g_force_cfg = -1;  // test / tuning hook: -1 = heuristic
 
+template <int TN>
+static bnn_status launch_direct(GemmParams &p, hipStream_t s) {
+  p.tilesM = (p.M + TM - 1) / TM;
+  p.tilesN = (p.N + 64 * TN - 1) / (64 * TN);
+  const int64_t waves = (int64_t)p.tilesM * p.tilesN;
+  const int64_t blocks = (waves + 3) / 4;
+  if (blocks > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+  ProfScope ps(KID_XNOR_GEMM_SMALL, s);
+  if (waves >= 2 * 1024)
+    hipLaunchKernelGGL((xnor_gemm_direct_kernel<TN, 4, 1>), dim3((unsigned)blocks), dim3(256), 0, s, p);
+  else
+    hipLaunchKernelGGL((xnor_gemm_direct_kernel<TN, 4, 0>), dim3((unsigned)blocks), dim3(256), 0, s, p);
+  return launch_status();
+}
+
 bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s) {
   int cfg = g_force_cfg;
+  if (bmode == 0 && emode == 0 && (cfg == 7 || cfg == 8 || cfg < 0)) {
+    // Too few 32 x 128 tiles to give every SIMD two waves of the LDS-staged kernel: use
+    // independent waves on 8 x 128 (or 8 x 64) tiles instead.
+    const int64_t t32 = (int64_t)((p.M + 31) / 32) * ((p.N + 127) / 128);
+    const int64_t w128 = (int64_t)((p.M + 7) / 8) * ((p.N + 127) / 128);
+    if (cfg == 8 || (cfg < 0 && t32 < 512 && w128 >= 2048)) return launch_direct<2>(p, s);
+    if (cfg == 7 || (cfg < 0 && t32 < 512)) return launch_direct<1>(p, s);
+  }
   if (emode == 1) {
     // tiles the packed epilogue is written for: 64 x 256 (3), 64 x 128 (6), 32 x 256 (1), 32 x 128 (4);
     // pooling needs four columns per lane (3 or 1)
     const bool ok = p.g.pool ? (cfg == 3 || cfg == 1) : (cfg == 3 || cfg == 6 || cfg == 1 || cfg == 4);
-    if (!ok) {
-      const int64_t t256e = (int64_t)((p.M + 63) / 64) * ((p.N + 255) / 256);
-      cfg = t256e >= 768 ? 3 : 1;
-    }
+    if (!ok) cfg = 3;  // 64 x 256: fastest at every layer shape measured
   }
-  if (bmode == 1 && (cfg == 0)) cfg = 3;        // no implicit-GEMM instantiation of the 32 x 512 tile
   if (cfg < 0) {
     // Measured on MI355X: 64 x 256 (TN = 4, eight waves per workgroup, six per SIMD) is the
     // fastest tile when there are enough of them; smaller problems take finer tiles so that
@@ -577,7 +725,6 @@ bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s) {
     cfg = (p.M >= 64 && t256 >= 512) ? 3 : (p.M >= 64 && t128 >= 512) ? 6 : (t32 >= 512 ? 4 : 2);
   }
   switch (cfg) {
-    case 0: return launch_cfg<8, 4, 1, 2>(p, bmode, emode, s, KID_XNOR_GEMM);        // 32 x 512
     case 1: return launch_cfg<4, 4, 1, 4>(p, bmode, emode, s, KID_XNOR_GEMM);        // 32 x 256
     case 2: return launch_cfg<1, 4, 1, 4>(p, bmode, emode, s, KID_XNOR_GEMM_SMALL);  // 32 x 64
     case 3: return launch_cfg<4, 8, 1, 6>(p, bmode, emode, s, KID_XNOR_GEMM);        // 64 x 256
