@@ -136,6 +136,129 @@ __global__ __launch_bounds__(256) void conv2d_f32_sign_kernel(const float *__res
   }
 }
 
+// 3x3x3 specialization (K = 27).  Each lane owns TWO output pixels (p and p + half), so one
+// set of scalar weight loads feeds 54 fused multiply-adds, and the loads of the next channel
+// (27 weights, scale, bias: 29 SGPRs) are issued before the current channel is computed: the
+// scalar-memory latency is covered by compute instead of being waited for per channel.
+// Channels run from high to low inside each group of 32, so the sign bit is shifted in with a
+// single add-with-carry (word = 2*word + bit).  Loads, wait and carry trick are inline asm;
+// the last load statement of a set names the first tap of both pixels as in/out operand, which
+// keeps the multiply-adds of the channel being computed behind the loads of the next one.
+// Every SGPR an in-flight load will write is an operand of the wait that follows, so it stays
+// reserved until the data has arrived.
+using f32s_u32x2 = uint32_t __attribute__((ext_vector_type(2)));
+using f32s_u32x8 = uint32_t __attribute__((ext_vector_type(8)));
+using f32s_u32x16 = uint32_t __attribute__((ext_vector_type(16)));
+struct F32sWSet {
+  f32s_u32x16 a;  // taps 0..15
+  f32s_u32x8 b;   // taps 16..23
+  f32s_u32x2 c;   // taps 24, 25
+  uint32_t d;     // tap 26
+  uint32_t sc, bi;
+};
+
+__device__ __forceinline__ uint64_t f32s_uniform64(const void *ptr) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)ptr);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uintptr_t)ptr >> 32));
+  return ((uint64_t)hi << 32) | (uint64_t)lo;
+}
+
+#define F32S_LOAD(S, ch)                                                                                  \
+  do {                                                                                                    \
+    const uint32_t ch_ = (uint32_t)__builtin_amdgcn_readfirstlane((int)(ch));                             \
+    const uint64_t wa_ = wbase + (uint64_t)ch_ * 108u;                                                    \
+    const uint64_t sa_ = sbase + (uint64_t)ch_ * 4u;                                                      \
+    const uint64_t ba_ = bbase + (uint64_t)ch_ * 4u;                                                      \
+    asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=s"(S.a) : "s"(wa_));                                   \
+    asm volatile("s_load_dwordx8 %0, %1, 0x40" : "=s"(S.b) : "s"(wa_));                                   \
+    asm volatile("s_load_dwordx2 %0, %1, 0x60" : "=s"(S.c) : "s"(wa_));                                   \
+    asm volatile("s_load_dword %0, %1, 0x68" : "=s"(S.d) : "s"(wa_));                                     \
+    asm volatile("s_load_dword %0, %1, 0x0" : "=s"(S.sc) : "s"(sa_));                                     \
+    asm volatile("s_load_dword %0, %3, 0x0" : "=s"(S.bi), "+v"(xv[0][0]), "+v"(xv[1][0]) : "s"(ba_));     \
+  } while (0)
+#define F32S_WAIT(S) \
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(S.a), "+s"(S.b), "+s"(S.c), "+s"(S.d), "+s"(S.sc), "+s"(S.bi))
+
+__global__ __launch_bounds__(256) void conv2d_f32_sign27_kernel(const float *__restrict__ x, const float *w_, int H,
+                                                                int W, int D, int sH, int sW, int pH, int pW,
+                                                                int OH, int OW, const float *scale_,
+                                                                const float *bias_, uint64_t *__restrict__ outp,
+                                                                int cw_out, FastDiv divOW, FastDiv divOH,
+                                                                uint32_t total_pix, uint32_t half) {
+  const uint32_t gid = blockIdx.x * 256u + threadIdx.x;
+  const uint64_t wbase = f32s_uniform64(w_), sbase = f32s_uniform64(scale_), bbase = f32s_uniform64(bias_);
+  // pixel q of this lane: gid + q * half (the second may not exist)
+  float xv[2][27];
+  bool pv[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const uint32_t p = gid + (uint32_t)q * half;
+    pv[q] = gid < half && p < total_pix;
+    const uint32_t pc = pv[q] ? p : 0u;
+    const uint32_t t = fdiv(pc, divOW);
+    const uint32_t ow = pc - t * OW;
+    const uint32_t n = fdiv(t, divOH);
+    const uint32_t oh = t - n * OH;
+    const int ih0 = (int)(oh * sH) - pH, iw0 = (int)(ow * sW) - pW;
+    const float *xn = x + (size_t)n * 3 * H * W;
+#pragma unroll
+    for (int k = 0; k < 27; ++k) {
+      const int c = k / 9, r = k % 9;
+      const int ih = ih0 + r / 3, iw = iw0 + r % 3;
+      float v = 0.0f;
+      if (pv[q] && ih >= 0 && ih < H && iw >= 0 && iw < W) v = xn[((size_t)c * H + ih) * W + iw];
+      xv[q][k] = v;
+    }
+  }
+  uint32_t word[2] = {0u, 0u}, hi[2] = {0u, 0u};
+  auto compute = [&](const F32sWSet &S, int ch) {
+    const float sc = __uint_as_float(S.sc), bi = __uint_as_float(S.bi);
+    // the two pixels' chains advance together: every multiply-add has an independent neighbour
+    float acc[2] = {0.0f, 0.0f};
+#pragma unroll
+    for (int k = 0; k < 27; ++k) {
+      const float wk = __uint_as_float(k < 16 ? S.a[k & 15] : k < 24 ? S.b[k & 7] : k < 26 ? S.c[k & 1] : S.d);
+#pragma unroll
+      for (int q = 0; q < 2; ++q) acc[q] = fmaf(xv[q][k], wk, acc[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const float y = fmaf(sc, acc[q], bi);
+      // word = 2 * word + (y >= 0)
+      asm("v_cmp_le_f32 vcc, 0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(word[q]) : "v"(y) : "vcc");
+    }
+    if ((ch & 31) == 0) {
+      // a group of 32 channels is complete: drop the bits of channels past D, emit
+      const int g = ch >> 5;
+      const int left = D - ch;  // real channels in this group
+      const uint32_t vm = left >= 32 ? 0xffffffffu : ((1u << left) - 1u);
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const uint32_t wv = left > 0 ? (word[q] & vm) : 0u;
+        if (g & 1) {
+          hi[q] = wv;  // channels descend: the upper half of a word is finished first
+        } else {
+          const uint32_t p = gid + (uint32_t)q * half;
+          if (pv[q]) outp[(size_t)p * cw_out + (g >> 1)] = ((uint64_t)hi[q] << 32) | wv;
+        }
+        word[q] = 0u;
+      }
+    }
+  };
+  const int Dpad = cw_out * 64;
+  const int last = D - 1;
+  F32sWSet SA, SB;
+  F32S_LOAD(SA, (Dpad - 1 < last ? Dpad - 1 : last));
+  for (int ch = Dpad - 1; ch > 0; ch -= 2) {
+    F32S_WAIT(SA);
+    F32S_LOAD(SB, (ch - 1 < last ? ch - 1 : last));
+    compute(SA, ch);
+    F32S_WAIT(SB);
+    if (ch >= 2) F32S_LOAD(SA, (ch - 2 < last ? ch - 2 : last));
+    compute(SB, ch - 1);
+  }
+}
+
 // Filter bank of a fully-connected layer whose input is a flattened NCHW map [C, H, W],
 // re-ordered to the packed NHWC bit order (h, w, c) of the activations: a common
 // permutation of the reduction axis leaves the result unchanged.
@@ -231,15 +354,19 @@ extern "C" bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N,
   hipStream_t s = (hipStream_t)stream;
   {
     ProfScope ps(KID_CONV_F32_SIGN, s);
-    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
-    if (K == 27)
-      hipLaunchKernelGGL(conv2d_f32_sign_kernel<27>, grid, block, 0, s, x, w, C, H, W, D, kH, kW, sH, sW, pH, pW,
-                         (int)OH, (int)OW, scale, bias, out_packed, (int)bnn_packed_words(D), FastDiv((uint32_t)OW),
-                         FastDiv((uint32_t)OH), (uint32_t)total, (int)K);
-    else
+    const dim3 block(256);
+    if (K == 27 && C == 3 && kH == 3 && kW == 3) {
+      const int64_t half = (total + 1) / 2;
+      const dim3 grid((unsigned)((half + 255) / 256));
+      hipLaunchKernelGGL(conv2d_f32_sign27_kernel, grid, block, 0, s, x, w, H, W, D, sH, sW, pH, pW, (int)OH, (int)OW,
+                         scale, bias, out_packed, (int)bnn_packed_words(D), FastDiv((uint32_t)OW),
+                         FastDiv((uint32_t)OH), (uint32_t)total, (uint32_t)half);
+    } else {
+      const dim3 grid((unsigned)((total + 255) / 256));
       hipLaunchKernelGGL(conv2d_f32_sign_kernel<0>, grid, block, 0, s, x, w, C, H, W, D, kH, kW, sH, sW, pH, pW,
                          (int)OH, (int)OW, scale, bias, out_packed, (int)bnn_packed_words(D), FastDiv((uint32_t)OW),
                          FastDiv((uint32_t)OH), (uint32_t)total, (int)K);
+    }
   }
   return launch_status();
 }

@@ -79,40 +79,85 @@ __global__ __launch_bounds__(256) void conv2d_f32_kernel(const float *__restrict
   }
 }
 
-// One workgroup per (row m, group of FC_NB outputs).  x and w are staged through LDS in
-// K-chunks with coalesced loads; thread j < FC_NB then runs the sequential fma chain of
-// output n0 + j over the chunk, so the summation order over k is ascending as specified.
+// One workgroup per (16 rows of x, 16 outputs).  The whole K extent (up to FC_KC) of those
+// rows of x and w is staged in LDS with every global load in flight at once, so memory latency
+// is paid once; then thread (output j, row r) runs the sequential fma chain over k, which is
+// the floor for this layer (the summation order over k is ascending as specified, so a chain
+// cannot be split).  Longer rows take several passes over the two LDS tiles.
+constexpr int FC_ROWS = 16;
 constexpr int FC_NB = 16;
-constexpr int FC_KC = 256;
+constexpr int FC_KC = 1024;
+constexpr int FC_RS = FC_KC + 4;  // row stride in floats: 16-byte reads of different rows spread over the banks
 __global__ __launch_bounds__(256) void fc_f32_kernel(const float *__restrict__ x, const float *__restrict__ w,
                                                      const float *__restrict__ bias, int64_t M, int64_t K, int64_t N,
                                                      int sign_input, float *__restrict__ out, int n_groups) {
-  __shared__ float sx[FC_KC];
-  __shared__ float sw[FC_NB][FC_KC + 1];
-  const int64_t m = blockIdx.x / n_groups;
+  __shared__ __attribute__((aligned(16))) float sx[FC_ROWS * FC_RS];
+  __shared__ __attribute__((aligned(16))) float sw[FC_NB * FC_RS];
+  const int64_t m0 = (int64_t)(blockIdx.x / n_groups) * FC_ROWS;
   const int64_t n0 = (int64_t)(blockIdx.x % n_groups) * FC_NB;
   const int tid = threadIdx.x;
+  const int r = tid & 15, j = tid >> 4;
+  const bool vec = (K & 3) == 0;  // rows start 16-byte aligned (the bases are)
   float acc = 0.0f;
   for (int64_t k0 = 0; k0 < K; k0 += FC_KC) {
     const int kc = (int)((K - k0) < FC_KC ? (K - k0) : FC_KC);
-    if (tid < kc) {
-      float xv = x[m * K + k0 + tid];
-      if (sign_input) xv = xv >= 0.0f ? 1.0f : -1.0f;
-      sx[tid] = xv;
-    }
-    for (int idx = tid; idx < FC_NB * FC_KC; idx += 256) {
-      const int j = idx / FC_KC, kk = idx % FC_KC;
-      if (n0 + j < N && kk < kc) sw[j][kk] = w[(n0 + j) * K + k0 + kk];
+    if (vec) {
+      constexpr int Q = FC_KC / 4;             // 16-byte pieces per row
+      constexpr int PER = FC_ROWS * Q / 256;   // pieces per thread and operand
+      float4 vx[PER], vw[PER];
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const int idx = i * 256 + tid;
+        const int rr = idx / Q, kk = (idx % Q) * 4;
+        vx[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        vw[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (kk < kc) {
+          if (m0 + rr < M) vx[i] = *reinterpret_cast<const float4 *>(x + (m0 + rr) * K + k0 + kk);
+          if (n0 + rr < N) vw[i] = *reinterpret_cast<const float4 *>(w + (n0 + rr) * K + k0 + kk);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const int idx = i * 256 + tid;
+        const int rr = idx / Q, kk = (idx % Q) * 4;
+        float4 v = vx[i];
+        if (sign_input) {
+          v.x = v.x >= 0.0f ? 1.0f : -1.0f; v.y = v.y >= 0.0f ? 1.0f : -1.0f;
+          v.z = v.z >= 0.0f ? 1.0f : -1.0f; v.w = v.w >= 0.0f ? 1.0f : -1.0f;
+        }
+        *reinterpret_cast<float4 *>(&sx[rr * FC_RS + kk]) = v;
+        *reinterpret_cast<float4 *>(&sw[rr * FC_RS + kk]) = vw[i];
+      }
+    } else {
+      for (int idx = tid; idx < FC_ROWS * FC_KC; idx += 256) {
+        const int rr = idx / FC_KC, kk = idx % FC_KC;
+        float xv = 0.0f, wv = 0.0f;
+        if (kk < kc) {
+          if (m0 + rr < M) xv = x[(m0 + rr) * K + k0 + kk];
+          if (n0 + rr < N) wv = w[(n0 + rr) * K + k0 + kk];
+          if (sign_input) xv = xv >= 0.0f ? 1.0f : -1.0f;
+        }
+        sx[rr * FC_RS + kk] = xv;
+        sw[rr * FC_RS + kk] = wv;
+      }
     }
     __syncthreads();
-    if (tid < FC_NB && n0 + tid < N) {
-      for (int kk = 0; kk < kc; ++kk) acc = fmaf(sx[kk], sw[tid][kk], acc);
+    const float *px = &sx[r * FC_RS], *pw = &sw[j * FC_RS];
+    int kk = 0;
+    for (; kk + 4 <= kc; kk += 4) {
+      const float4 a = *reinterpret_cast<const float4 *>(px + kk);
+      const float4 b = *reinterpret_cast<const float4 *>(pw + kk);
+      acc = fmaf(a.x, b.x, acc);
+      acc = fmaf(a.y, b.y, acc);
+      acc = fmaf(a.z, b.z, acc);
+      acc = fmaf(a.w, b.w, acc);
     }
+    for (; kk < kc; ++kk) acc = fmaf(px[kk], pw[kk], acc);
     __syncthreads();
   }
-  if (tid < FC_NB && n0 + tid < N) {
-    if (bias) acc = acc + bias[n0 + tid];
-    out[m * N + n0 + tid] = acc;
+  if (m0 + r < M && n0 + j < N) {
+    if (bias) acc = acc + bias[n0 + j];
+    out[(m0 + r) * N + n0 + j] = acc;
   }
 }
 
@@ -281,11 +326,12 @@ extern "C" bnn_status bnn_fc_f32(const float *x, const float *w, const float *bi
   if (!x || !w || !out) return BNN_ERR_NULL;
   if (!aligned16(x) || !aligned16(w) || !aligned16(out)) return BNN_ERR_ALIGN;
   const int64_t n_groups = (N + FC_NB - 1) / FC_NB;
-  if (M * n_groups > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+  const int64_t m_groups = (M + FC_ROWS - 1) / FC_ROWS;
+  if (m_groups * n_groups > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
   {
     ProfScope ps(KID_FC_F32, s);
-    hipLaunchKernelGGL(fc_f32_kernel, dim3((unsigned)(M * n_groups)), dim3(256), 0, s, x, w, bias, M, K, N, sign_input,
+    hipLaunchKernelGGL(fc_f32_kernel, dim3((unsigned)(m_groups * n_groups)), dim3(256), 0, s, x, w, bias, M, K, N, sign_input,
                        out, (int)n_groups);
   }
   return launch_status();
