@@ -136,16 +136,17 @@ __global__ __launch_bounds__(256) void conv2d_f32_sign_kernel(const float *__res
   }
 }
 
-// 3x3x3 specialization (K = 27).  Each lane owns TWO output pixels (p and p + half), so one
-// set of scalar weight loads feeds 54 fused multiply-adds, and the loads of the next channel
+// 3x3x3 specialization (K = 27).  Each lane owns F32S_NP output pixels (p + q * part), so one
+// set of scalar weight loads feeds 27 * F32S_NP fused multiply-adds, and the loads of the next channel
 // (27 weights, scale, bias: 29 SGPRs) are issued before the current channel is computed: the
 // scalar-memory latency is covered by compute instead of being waited for per channel.
 // Channels run from high to low inside each group of 32, so the sign bit is shifted in with a
 // single add-with-carry (word = 2*word + bit).  Loads, wait and carry trick are inline asm;
-// the last load statement of a set names the first tap of both pixels as in/out operand, which
+// the last load statement of a set names the first tap of the first pixel as in/out operand, which
 // keeps the multiply-adds of the channel being computed behind the loads of the next one.
 // Every SGPR an in-flight load will write is an operand of the wait that follows, so it stays
 // reserved until the data has arrived.
+constexpr int F32S_NP = 2;
 using f32s_u32x2 = uint32_t __attribute__((ext_vector_type(2)));
 using f32s_u32x8 = uint32_t __attribute__((ext_vector_type(8)));
 using f32s_u32x16 = uint32_t __attribute__((ext_vector_type(16)));
@@ -163,18 +164,17 @@ __device__ __forceinline__ uint64_t f32s_uniform64(const void *ptr) {
   return ((uint64_t)hi << 32) | (uint64_t)lo;
 }
 
-#define F32S_LOAD(S, ch)                                                                                  \
-  do {                                                                                                    \
-    const uint32_t ch_ = (uint32_t)__builtin_amdgcn_readfirstlane((int)(ch));                             \
-    const uint64_t wa_ = wbase + (uint64_t)ch_ * 108u;                                                    \
-    const uint64_t sa_ = sbase + (uint64_t)ch_ * 4u;                                                      \
-    const uint64_t ba_ = bbase + (uint64_t)ch_ * 4u;                                                      \
-    asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=s"(S.a) : "s"(wa_));                                   \
-    asm volatile("s_load_dwordx8 %0, %1, 0x40" : "=s"(S.b) : "s"(wa_));                                   \
-    asm volatile("s_load_dwordx2 %0, %1, 0x60" : "=s"(S.c) : "s"(wa_));                                   \
-    asm volatile("s_load_dword %0, %1, 0x68" : "=s"(S.d) : "s"(wa_));                                     \
-    asm volatile("s_load_dword %0, %1, 0x0" : "=s"(S.sc) : "s"(sa_));                                     \
-    asm volatile("s_load_dword %0, %3, 0x0" : "=s"(S.bi), "+v"(xv[0][0]), "+v"(xv[1][0]) : "s"(ba_));     \
+#define F32S_LOAD(S, ch)                                                                                   \
+  do {                                                                                                     \
+    const uint32_t ch_ = (uint32_t)__builtin_amdgcn_readfirstlane((int)(ch));                              \
+    const uint32_t o0_ = ch_ * 108u, o1_ = o0_ + 0x40u, o2_ = o0_ + 0x60u, o3_ = o0_ + 0x68u;              \
+    const uint32_t o4_ = ch_ * 4u;                                                                         \
+    asm volatile("s_load_dwordx16 %0, %1, %2" : "=s"(S.a) : "s"(wbase), "s"(o0_));                         \
+    asm volatile("s_load_dwordx8 %0, %1, %2" : "=s"(S.b) : "s"(wbase), "s"(o1_));                          \
+    asm volatile("s_load_dwordx2 %0, %1, %2" : "=s"(S.c) : "s"(wbase), "s"(o2_));                          \
+    asm volatile("s_load_dword %0, %1, %2" : "=s"(S.d) : "s"(wbase), "s"(o3_));                            \
+    asm volatile("s_load_dword %0, %1, %2" : "=s"(S.sc) : "s"(sbase), "s"(o4_));                           \
+    asm volatile("s_load_dword %0, %2, %3" : "=s"(S.bi), "+v"(xv[0][0]) : "s"(bbase), "s"(o4_));           \
   } while (0)
 #define F32S_WAIT(S) \
   asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(S.a), "+s"(S.b), "+s"(S.c), "+s"(S.d), "+s"(S.sc), "+s"(S.bi))
@@ -184,16 +184,16 @@ __global__ __launch_bounds__(256) void conv2d_f32_sign27_kernel(const float *__r
                                                                 int OH, int OW, const float *scale_,
                                                                 const float *bias_, uint64_t *__restrict__ outp,
                                                                 int cw_out, FastDiv divOW, FastDiv divOH,
-                                                                uint32_t total_pix, uint32_t half) {
+                                                                uint32_t total_pix, uint32_t part) {
   const uint32_t gid = blockIdx.x * 256u + threadIdx.x;
   const uint64_t wbase = f32s_uniform64(w_), sbase = f32s_uniform64(scale_), bbase = f32s_uniform64(bias_);
-  // pixel q of this lane: gid + q * half (the second may not exist)
-  float xv[2][27];
-  bool pv[2];
+  // pixel q of this lane: gid + q * part (the later ones may not exist)
+  float xv[F32S_NP][27];
+  bool pv[F32S_NP];
 #pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const uint32_t p = gid + (uint32_t)q * half;
-    pv[q] = gid < half && p < total_pix;
+  for (int q = 0; q < F32S_NP; ++q) {
+    const uint32_t p = gid + (uint32_t)q * part;
+    pv[q] = gid < part && p < total_pix;
     const uint32_t pc = pv[q] ? p : 0u;
     const uint32_t t = fdiv(pc, divOW);
     const uint32_t ow = pc - t * OW;
@@ -210,19 +210,23 @@ __global__ __launch_bounds__(256) void conv2d_f32_sign27_kernel(const float *__r
       xv[q][k] = v;
     }
   }
-  uint32_t word[2] = {0u, 0u}, hi[2] = {0u, 0u};
+  uint32_t word[F32S_NP], hi[F32S_NP];
+#pragma unroll
+  for (int q = 0; q < F32S_NP; ++q) word[q] = hi[q] = 0u;
   auto compute = [&](const F32sWSet &S, int ch) {
     const float sc = __uint_as_float(S.sc), bi = __uint_as_float(S.bi);
-    // the two pixels' chains advance together: every multiply-add has an independent neighbour
-    float acc[2] = {0.0f, 0.0f};
+    // the pixels' chains advance together: every multiply-add has independent neighbours
+    float acc[F32S_NP];
+#pragma unroll
+    for (int q = 0; q < F32S_NP; ++q) acc[q] = 0.0f;
 #pragma unroll
     for (int k = 0; k < 27; ++k) {
       const float wk = __uint_as_float(k < 16 ? S.a[k & 15] : k < 24 ? S.b[k & 7] : k < 26 ? S.c[k & 1] : S.d);
 #pragma unroll
-      for (int q = 0; q < 2; ++q) acc[q] = fmaf(xv[q][k], wk, acc[q]);
+      for (int q = 0; q < F32S_NP; ++q) acc[q] = fmaf(xv[q][k], wk, acc[q]);
     }
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
+    for (int q = 0; q < F32S_NP; ++q) {
       const float y = fmaf(sc, acc[q], bi);
       // word = 2 * word + (y >= 0)
       asm("v_cmp_le_f32 vcc, 0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(word[q]) : "v"(y) : "vcc");
@@ -233,12 +237,12 @@ __global__ __launch_bounds__(256) void conv2d_f32_sign27_kernel(const float *__r
       const int left = D - ch;  // real channels in this group
       const uint32_t vm = left >= 32 ? 0xffffffffu : ((1u << left) - 1u);
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
+      for (int q = 0; q < F32S_NP; ++q) {
         const uint32_t wv = left > 0 ? (word[q] & vm) : 0u;
         if (g & 1) {
           hi[q] = wv;  // channels descend: the upper half of a word is finished first
         } else {
-          const uint32_t p = gid + (uint32_t)q * half;
+          const uint32_t p = gid + (uint32_t)q * part;
           if (pv[q]) outp[(size_t)p * cw_out + (g >> 1)] = ((uint64_t)hi[q] << 32) | wv;
         }
         word[q] = 0u;
@@ -356,11 +360,11 @@ extern "C" bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N,
     ProfScope ps(KID_CONV_F32_SIGN, s);
     const dim3 block(256);
     if (K == 27 && C == 3 && kH == 3 && kW == 3) {
-      const int64_t half = (total + 1) / 2;
-      const dim3 grid((unsigned)((half + 255) / 256));
+      const int64_t part = (total + F32S_NP - 1) / F32S_NP;
+      const dim3 grid((unsigned)((part + 255) / 256));
       hipLaunchKernelGGL(conv2d_f32_sign27_kernel, grid, block, 0, s, x, w, H, W, D, sH, sW, pH, pW, (int)OH, (int)OW,
                          scale, bias, out_packed, (int)bnn_packed_words(D), FastDiv((uint32_t)OW),
-                         FastDiv((uint32_t)OH), (uint32_t)total, (uint32_t)half);
+                         FastDiv((uint32_t)OH), (uint32_t)total, (uint32_t)part);
     } else {
       const dim3 grid((unsigned)((total + 255) / 256));
       hipLaunchKernelGGL(conv2d_f32_sign_kernel<0>, grid, block, 0, s, x, w, C, H, W, D, kH, kW, sH, sW, pH, pW,

@@ -261,6 +261,39 @@ __global__ __launch_bounds__(256) void valu_rows_probe_kernel(int32_t *__restric
   sink[tid] = tot;
 }
 
+// fp32 multiply-add throughput: 128 v_fmac_f32 per round on 16 independent accumulators.
+// SG = 1 takes the multiplier from an SGPR (as the real-valued first layer does), SG = 0
+// from a VGPR.
+template <int SG>
+__global__ __launch_bounds__(256) void fma_probe_kernel(int32_t *__restrict__ sink, int iters, uint32_t seed) {
+  const uint32_t tid = blockIdx.x * 256u + threadIdx.x;
+  float x[8], acc[16];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) x[j] = 1.0f + (float)((tid + j) & 7u) * 0.125f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+  float wv[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) wv[j] = 0.5f + (float)((SG ? seed : tid) + j) * 1e-3f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 8; ++r)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        if constexpr (SG) {
+          const float ws = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(wv[(r + i) & 7])));
+          asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(acc[i]) : "s"(ws), "v"(x[r]));
+        } else {
+          asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(acc[i]) : "v"(wv[(r + i) & 7]), "v"(x[r]));
+        }
+      }
+  }
+  float tot = 0.0f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) tot += acc[i];
+  sink[tid] = (int32_t)__float_as_uint(tot);
+}
+
 __global__ __launch_bounds__(256) void copy_probe_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
                                                          size_t n16) {
   size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
@@ -356,6 +389,8 @@ extern "C" bnn_status bnn_valu_peak_probe(int32_t *sink, int blocks, int iters, 
       case 6: hipLaunchKernelGGL(valu_rows_probe_kernel<4>, g, b, 0, s, sink, iters / 4, 1u); break;
       case 7: hipLaunchKernelGGL((valu_rows_probe_kernel<2, 1>), g, b, 0, s, sink, iters / 2, 1u); break;
       case 8: hipLaunchKernelGGL((valu_rows_probe_kernel<4, 1>), g, b, 0, s, sink, iters / 4, 1u); break;
+      case 9: hipLaunchKernelGGL(fma_probe_kernel<0>, g, b, 0, s, sink, iters, 1u); break;
+      case 10: hipLaunchKernelGGL(fma_probe_kernel<1>, g, b, 0, s, sink, iters, 1u); break;
       default: hipLaunchKernelGGL(valu_probe_kernel<0>, g, b, 0, s, sink, iters, 1u); break;
     }
   }
