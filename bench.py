@@ -2,10 +2,13 @@
 """Benchmark of the binarized conv / GEMM path on one MI355X.
 
 A "step" is one pass of the whole hot path over one batch of synthetic input.  The
-default workload is the binarized VGG-small stack at batch 256 (the one configuration
-that exercises every step: sign-encode, packed im2col, XOR-popcount GEMM, NCHW store,
-fp32 epilogue and the glue kernels).  Inputs and pre-encoded weights are resident in
-HBM before the timed region.  Prints ONE JSON line.
+default workload is the binarized VGG-small stack at batch 256: real-valued first layer
+with sign-packed output, six binarized 3x3 convolutions as implicit XOR-popcount GEMMs over
+packed NHWC activations (pool + scale/bias + sign + pack in the GEMM epilogue), the binarized
+FC layer with fp32 epilogue and the fp32 classifier.  `--stack unfused` runs the same network
+through bnn_conv2d (sign-encode, packed operands, int32 NCHW maps, separate glue kernels).
+Inputs and pre-encoded weights are resident in HBM before the timed region.  Prints ONE JSON
+line; the other configurations, the streaming kernels and the MFMA ablation ride along in it.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4|cfg2|cfg3|cfg5a|cfg5b]
 """

@@ -8,8 +8,8 @@
 //     in flight per wave and the 16 words leave in one contiguous 128-byte store.
 //   * NCHW images: the packing axis (channel) is strided by H*W floats, so lanes
 //     run along pixels (coalesced 256-byte loads per channel) and every lane
-//     shift-ORs its own words over a channel loop, then stores its ceil(C/64)
-//     words contiguously (packed NHWC).
+//     shift-ORs 32 channels at a time; the four waves of a workgroup share the
+//     channel axis of 64 pixels and assemble the packed NHWC words through LDS.
 #include "common.h"
 
 namespace bnn {
@@ -84,73 +84,70 @@ __global__ __launch_bounds__(256) void pack_conv_weight_kernel(const float *__re
 // NCHW fp32 -> packed pixels [N*OHp*OWp, Cw].  Output pixel (n, oh, ow) samples input
 // pixel (oh*sH, ow*sW); with sH = sW = 1 and OHp = H, OWp = W this is the packed NHWC
 // image, with the strides of a 1x1 / pad-0 convolution it is the patch matrix itself.
-template <int CW>
+//
+// A workgroup owns 64 consecutive output pixels (one per lane).  The channel axis is cut
+// into granules of 32 channels (one half word) dealt round-robin to the workgroup's four
+// waves, so four times as many waves stream as there are pixel groups and each lane has
+// 32 independent plane-strided loads in flight per granule.  The half words meet in LDS
+// and leave as one contiguous run of 64 * Cw words.
+constexpr int ENCN_PIX = 64;
 __global__ __launch_bounds__(256) void encode_nchw_kernel(const float *__restrict__ x, int C, int H, int W,
-                                                          int OHp, int OWp, int sH, int sW,
-                                                          FastDiv divOW, FastDiv divOH,
-                                                          uint64_t *__restrict__ out, uint32_t total_pix,
-                                                          int cw_runtime) {
-  const uint32_t p = blockIdx.x * 256u + threadIdx.x;
-  if (p >= total_pix) return;
-  const uint32_t t = fdiv(p, divOW);
-  const uint32_t ow = p - t * OWp;
+                                                          int OHp, int OWp, int sH, int sW, FastDiv divOW,
+                                                          FastDiv divOH, uint64_t *__restrict__ out,
+                                                          uint32_t total_pix, int Cw) {
+  extern __shared__ uint32_t s_half[];  // [64 pixels][2*Cw + 1]
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t p0 = blockIdx.x * (uint32_t)ENCN_PIX;
+  const uint32_t p = p0 + lane;
+  const uint32_t pc = p < total_pix ? p : total_pix - 1;  // lanes past the end re-read the last pixel
+  const uint32_t t = fdiv(pc, divOW);
+  const uint32_t ow = pc - t * OWp;
   const uint32_t n = fdiv(t, divOH);
   const uint32_t oh = t - n * OHp;
   const size_t plane = (size_t)H * W;
-  const float *px = x + (size_t)n * C * plane + (size_t)(oh * sH) * W + (size_t)ow * sW;
-  const int Cw = CW > 0 ? CW : cw_runtime;
-  uint64_t *o = out + (size_t)p * Cw;
-  uint64_t words[CW > 0 ? CW : 1];
-#pragma unroll 1
-  for (int cw = 0; cw < Cw; ++cw) {
-    const int cbase = cw * 64;
-    uint32_t lo = 0, hi = 0;
-    if (cbase + 64 <= C) {
-      // full word: two groups of 32 channels, loads batched 16 at a time
+  // Address = wave-uniform 64-bit base (first image of the workgroup, channel plane) + a
+  // 32-bit per-lane byte offset: one VGPR of address per lane instead of one pair per load.
+  // The host checks that the offset (the images a workgroup can span) fits.
+  const uint32_t n0 = fdiv(fdiv(p0 < total_pix ? p0 : total_pix - 1, divOW), divOH);
+  const uint32_t off =
+      (uint32_t)(((size_t)(n - n0) * C * plane + (size_t)(oh * sH) * W + (size_t)ow * sW) * sizeof(float));
+  const char *xb = reinterpret_cast<const char *>(x + (size_t)n0 * C * plane);
+#define BNN_ENC_LD(c) (*reinterpret_cast<const float *>(xb + (size_t)(c) * plane * sizeof(float) + off))
+  const int G = 2 * Cw;  // granules, the last ones possibly partial or empty
+  const int rs = G + 1;
+  for (int g = wave; g < G; g += 4) {
+    const int c0 = g * 32;
+    const int left = C - c0;  // real channels in this granule
+    uint32_t acc = 0;
+    if (left >= 32) {
+      float v[32];
 #pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        uint32_t acc = 0;
+      for (int j = 0; j < 32; ++j) v[j] = BNN_ENC_LD(c0 + j);
 #pragma unroll
-        for (int c0 = 0; c0 < 32; c0 += 16) {
-          float v[16];
+      for (int j = 0; j < 32; ++j) acc |= (uint32_t)sign_bit(v[j]) << j;
+    } else if (left > 0) {
+      // channels past C re-read the last channel and are masked out
+      float v[32];
 #pragma unroll
-          for (int j = 0; j < 16; ++j) v[j] = px[(size_t)(cbase + half * 32 + c0 + j) * plane];
+      for (int j = 0; j < 32; ++j) v[j] = BNN_ENC_LD(c0 + (j < left ? j : left - 1));
 #pragma unroll
-          for (int j = 0; j < 16; ++j) acc |= (uint32_t)sign_bit(v[j]) << (c0 + j);
-        }
-        if (half == 0) lo = acc; else hi = acc;
-      }
-    } else {
-      for (int c = cbase; c < C; ++c) {
-        const uint32_t b = (uint32_t)sign_bit(px[(size_t)c * plane]);
-        const int bit = c - cbase;
-        if (bit < 32) lo |= b << bit; else hi |= b << (bit - 32);
-      }
+      for (int j = 0; j < 32; ++j) acc |= (uint32_t)sign_bit(v[j]) << j;
+      acc &= (1u << left) - 1u;
     }
-    const uint64_t word = ((uint64_t)hi << 32) | lo;
-    if (CW > 0) {
-      // static indexing only (cw is a loop counter of an un-unrolled loop)
-#pragma unroll
-      for (int j = 0; j < (CW > 0 ? CW : 1); ++j)
-        if (j == cw) words[j] = word;
-    } else {
-      o[cw] = word;
-    }
+    s_half[lane * rs + g] = acc;
   }
-  if (CW == 1) {
-    o[0] = words[0];
-  } else if (CW > 1) {
-    // CW is even here: 16-byte stores, contiguous across lanes
-    uint4 *o4 = reinterpret_cast<uint4 *>(o);
-#pragma unroll
-    for (int j = 0; j < (CW > 0 ? CW : 2) / 2; ++j) {
-      uint4 q;
-      q.x = (uint32_t)words[2 * j];
-      q.y = (uint32_t)(words[2 * j] >> 32);
-      q.z = (uint32_t)words[2 * j + 1];
-      q.w = (uint32_t)(words[2 * j + 1] >> 32);
-      o4[j] = q;
-    }
+#undef BNN_ENC_LD
+  __syncthreads();
+  // 64 * Cw words, contiguous in global memory from pixel p0
+  const uint32_t nwords = (uint32_t)ENCN_PIX * (uint32_t)Cw;
+  const uint64_t limit = (uint64_t)total_pix * (uint64_t)Cw;
+  uint64_t *o = out + (size_t)p0 * Cw;
+  for (uint32_t j = threadIdx.x; j < nwords; j += 256u) {
+    if ((uint64_t)p0 * Cw + j >= limit) break;
+    const uint32_t pix = j / (uint32_t)Cw, cw = j - pix * (uint32_t)Cw;
+    const uint32_t lo = s_half[pix * rs + 2 * cw], hi = s_half[pix * rs + 2 * cw + 1];
+    o[j] = ((uint64_t)hi << 32) | lo;
   }
 }
 
@@ -210,20 +207,16 @@ bnn_status launch_encode_nchw(const float *x, int N, int C, int H, int W, int OH
   if (total == 0) return BNN_OK;
   if (total > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   const int Cw = (int)bnn_packed_words(C);
-  const unsigned blocks = (unsigned)((total + 255) / 256);
+  const unsigned blocks = (unsigned)((total + ENCN_PIX - 1) / ENCN_PIX);
+  const size_t lds = (size_t)ENCN_PIX * (2 * Cw + 1) * sizeof(uint32_t);
+  if (lds > 64 * 1024) return BNN_ERR_UNSUPPORTED;  // C > 8128 channels
+  // 32-bit per-lane byte offsets: a workgroup's 64 pixels span at most `span` images past its first
+  const int64_t span = (ENCN_PIX + (int64_t)OHp * OWp - 1) / ((int64_t)OHp * OWp);
+  if ((span + 1) * (int64_t)C * H * W * 4 > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   FastDiv dOW((uint32_t)OWp), dOH((uint32_t)OHp);
   ProfScope ps(KID_ENCODE_NCHW, s);
-#define BNN_LAUNCH_ENC(CWT)                                                                              \
-  hipLaunchKernelGGL(encode_nchw_kernel<CWT>, dim3(blocks), dim3(256), 0, s, x, C, H, W, OHp, OWp, sH, sW, \
-                     dOW, dOH, out, (uint32_t)total, Cw)
-  switch (Cw) {
-    case 1: BNN_LAUNCH_ENC(1); break;
-    case 2: BNN_LAUNCH_ENC(2); break;
-    case 4: BNN_LAUNCH_ENC(4); break;
-    case 8: BNN_LAUNCH_ENC(8); break;
-    default: BNN_LAUNCH_ENC(0); break;
-  }
-#undef BNN_LAUNCH_ENC
+  hipLaunchKernelGGL(encode_nchw_kernel, dim3(blocks), dim3(256), lds, s, x, C, H, W, OHp, OWp, sH, sW, dOW, dOH, out,
+                     (uint32_t)total, Cw);
   return launch_status();
 }
 }  // namespace bnn
