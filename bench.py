@@ -228,6 +228,14 @@ def side_measurements():
         tot = sum(kt.values())
         res[f"{name}_im2col_total_GBs"] = round((x.numel() * 4 * (0.25 if shape.sH == 2 else 1.0) + shape.P * Kw * 8) / tot / 1e9, 1)
         del x
+    # the same two kernels on an input several times larger than the 256 MB last-level cache:
+    # encode 822 MB in / 26 MB out; gather 26 MB in / 231 MB out
+    x = torch.randn((256, 256, 56, 56), device=dev)
+    kt, _ = kernel_times(lambda: B.bnn_im2col_packed(x, 3, 3, (1, 1), (1, 1)), 5)
+    pix = 256 * 56 * 56
+    res["encode_nchw_822MB_GBs"] = round((x.numel() * 4 + pix * 4 * 8) / kt["encode_nchw"] / 1e9, 1)
+    res["im2col_gather_231MB_GBs"] = round((pix * 4 * 8 + pix * 36 * 8) / kt["im2col_gather"] / 1e9, 1)
+    del x
     # VALU probe: measured ceiling of xor + popcount-accumulate lane-ops
     blocks, iters = 256 * 16, 2000
     sink = torch.empty(blocks * 256, dtype=torch.int32, device=dev)
