@@ -29,8 +29,9 @@ HBM_PEAK_GBS = 8000.0
 VALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12  # 39.32
 BOPS_PER_LANEOP = 32.0  # 2 lane-instructions (xor, popcount-accumulate) per 32 bit-MACs = 64 binary ops
 
-# HBM bytes per GEMM launch from rocprofv3 counters (profiles/), valid for the default workload only.
-GEMM_TRAFFIC_BYTES = 73.2e6  # cfg-4 stack: 439 MB per step over 6 GEMM launches (profiles/xnor_gemm_cfg4_vgg_stack_b256.md)
+# HBM bytes per launch of xnor_gemm_kernel from rocprofv3 counters, valid for the default workload only
+# (profiles/xnor_gemm_cfg4_fused_stack_b256.md: FETCH_SIZE 4215.6 KiB x 2.00 + WRITE_SIZE 6316.3 KiB, five launches per step).
+GEMM_TRAFFIC_BYTES = 15.1e6
 
 
 def parse_args():
@@ -86,6 +87,33 @@ def kernel_times(fn, reps):
                 tot[name] = tot.get(name, 0.0) + ms / 1e3
                 cnt[name] = cnt.get(name, 0) + 1
         return {k: v / reps for k, v in tot.items()}, {k: v // reps for k, v in cnt.items()}
+    finally:
+        B.prof_enable(False)
+
+
+def gemm_launches(fn, shapes, reps):
+    """Per-launch (kernel name, seconds, lane-ops) of the step's GEMM launches, in launch order.
+
+    The library records one HIP-event pair per launch on the launch stream; the GEMM launches of a
+    step come in the order of `shapes`."""
+    import torch
+    from paper_1911_04477_amd import binding as B
+    B.prof_enable(True)
+    try:
+        fn()
+        torch.cuda.synchronize()
+        acc = None
+        for _ in range(reps):
+            B.prof_reset()
+            fn()
+            torch.cuda.synchronize()
+            rec = [(n, ms / 1e3) for n, ms in B.prof_records() if n.startswith("xnor_gemm")]
+            assert len(rec) == len(shapes), (len(rec), len(shapes))
+            if acc is None:
+                acc = [[n, 0.0] for n, _ in rec]
+            for a, (_, t) in zip(acc, rec):
+                a[1] += t
+        return [(n, t / reps, gemm_laneops(*sh)) for (n, t), sh in zip(acc, shapes)]
     finally:
         B.prof_enable(False)
 
@@ -302,19 +330,33 @@ def main():
     per_step = secs / args.steps
     value = wl["bops"] / per_step / 1e12
 
-    # dominant kernel: the XOR-popcount GEMM, timed with HIP events on the launch stream
-    kt, kc = kernel_times(wl["fn"], max(3, min(args.steps, 10)))
-    gemm_s = sum(v for k, v in kt.items() if k.startswith("xnor_gemm"))
-    gemm_launches = sum(v for k, v in kc.items() if k.startswith("xnor_gemm"))
-    lane_ops = sum(gemm_laneops(*sh) for sh in wl["gemm_shapes"])
-    achieved = lane_ops / gemm_s / 1e12
+    # dominant kernel: the XOR-popcount GEMM kernel that takes most of the step, timed per launch with
+    # HIP events on the launch stream
+    reps = max(3, min(args.steps, 10))
+    kt, kc = kernel_times(wl["fn"], reps)
+    launches = gemm_launches(wl["fn"], wl["gemm_shapes"], reps)
+    by_name = {}
+    for n, t, ops in launches:
+        e = by_name.setdefault(n, [0.0, 0.0, 0])
+        e[0] += t
+        e[1] += ops
+        e[2] += 1
+    dom = max(by_name, key=lambda n: by_name[n][0])
+    dom_s, dom_ops, dom_n = by_name[dom]
+    gemm_s = sum(t for _, t, _ in launches)
+    achieved = dom_ops / dom_s / 1e12
+    default_wl = args.workload == "cfg4" and args.reading == "A" and args.stack == "fused"
     roofline = {
-        "kernel": "xnor_gemm", "bound": "alu", "achieved": round(achieved, 3), "peak": round(VALU_PEAK_TLANEOPS, 2),
+        "kernel": {"xnor_gemm": "xnor_gemm_kernel", "xnor_gemm_small": "xnor_gemm_direct_kernel / 32x64 tiles"}.get(dom, dom),
+        "bound": "alu", "achieved": round(achieved, 3), "peak": round(VALU_PEAK_TLANEOPS, 2),
         "unit": "Tlaneop/s", "frac": round(achieved / VALU_PEAK_TLANEOPS, 4),
-        "traffic": GEMM_TRAFFIC_BYTES if args.workload == "cfg4" and args.reading == "A" and args.stack == "fused" else None,
-        "launches_per_step": gemm_launches, "avg_launch_ms": round(gemm_s / max(gemm_launches, 1) * 1e3, 4),
+        "traffic": GEMM_TRAFFIC_BYTES if default_wl else None,
+        "launches_per_step": dom_n, "avg_launch_ms": round(dom_s / dom_n * 1e3, 4),
+        "per_launch": [{"kernel": n, "ms": round(t * 1e3, 4), "frac": round(ops / t / 1e12 / VALU_PEAK_TLANEOPS, 4)}
+                       for n, t, ops in launches],
         "gemm_only_TBOPS": round(wl["bops"] / gemm_s / 1e12, 2),
-        "note": "achieved = 2*M*N*ceil(K/32) lane-ops summed over the step's GEMM launches / their summed HIP-event time",
+        "note": "achieved = 2*M*N*ceil(K/32) lane-ops of the dominant kernel's launches in one step / their summed "
+                "HIP-event time; traffic = HBM bytes per launch of that kernel (rocprofv3 FETCH_SIZE*2.00 + WRITE_SIZE)",
     }
 
     cpu = None
