@@ -73,7 +73,7 @@ __device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv &f) {
 // row is word (w mod Cw) of tap (w div Cw), taps ordered (kh, kw).
 struct ConvGeom {
   const uint64_t *act;  // [Nimg, H, W, Cw]
-  int C, H, W, Cw, OH, OW, kW, sH, sW, pH, pW;
+  int Nimg, C, H, W, Cw, OH, OW, kH, kW, sH, sW, pH, pW;
   int pool;             // 0, or 2: columns are ordered window-major (see decode_col in gemm.hip)
   FastDiv divCw, divKW;
   FastDiv divOW, divOH; // output dims, or pooled output dims when pool == 2
@@ -104,7 +104,8 @@ struct GemmParams {
 };
 
 // Launch the exclusive-or / popcount GEMM described by p (tilesM / tilesN are filled in).
-// bmode 0: B is an explicit [N, ldb] matrix; 1: B is gathered from p.g (implicit GEMM).
+// bmode 0: B is an explicit [N, ldb] matrix; 1: B is gathered from p.g (implicit GEMM; the
+// launcher switches to the lean gather, kernel mode 2, when the geometry allows it).
 // emode 0: int32 / fp32 store; 1: packed sign(fma(scale, acc, bias)) store, optional 2x2 pool.
 bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s);
 

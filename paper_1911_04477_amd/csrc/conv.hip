@@ -15,14 +15,14 @@ namespace bnn {
 bnn_status launch_encode_nchw(const float *x, int N, int C, int H, int W, int OHp, int OWp, int sH, int sW,
                               uint64_t *out, hipStream_t s);
 
-static void fill_geom(ConvGeom &g, const uint64_t *act, int C, int H, int W, int kH, int kW, int sH, int sW, int pH,
+static void fill_geom(ConvGeom &g, const uint64_t *act, int N, int C, int H, int W, int kH, int kW, int sH, int sW, int pH,
                       int pW, int pool) {
   g.act = act;
-  g.C = C; g.H = H; g.W = W;
+  g.Nimg = N; g.C = C; g.H = H; g.W = W;
   g.Cw = (int)bnn_packed_words(C);
   g.OH = (int)bnn_conv_out_dim(H, kH, sH, pH);
   g.OW = (int)bnn_conv_out_dim(W, kW, sW, pW);
-  g.kW = kW; g.sH = sH; g.sW = sW; g.pH = pH; g.pW = pW;
+  g.kH = kH; g.kW = kW; g.sH = sH; g.sW = sW; g.pH = pH; g.pW = pW;
   g.pool = pool;
   g.divCw = FastDiv((uint32_t)g.Cw);
   g.divKW = FastDiv((uint32_t)kW);
@@ -59,7 +59,7 @@ static bnn_status conv_from_packed(const uint64_t *act, const uint64_t *w_packed
   p.OHW = (uint32_t)(OH * OW);
   p.divOHW = FastDiv((uint32_t)(OH * OW));
   p.img_stride = (int64_t)D * OH * OW;
-  fill_geom(p.g, act, C, H, W, kH, kW, sH, sW, pH, pW, pool);
+  fill_geom(p.g, act, N, C, H, W, kH, kW, sH, sW, pH, pW, pool);
   p.outp = out_packed;
   p.cw_out = (int)bnn_packed_words(D);
   return run_gemm(p, 1, out_packed ? 1 : 0, s);

@@ -50,6 +50,9 @@ __device__ __forceinline__ int popc_acc(uint32_t x, int acc) {
 // The K axis is consumed in chunks of KC = 8 dwords (256 bits); a wave owns TM = 8 rows.
 constexpr int KC = 8;
 constexpr int TM = 8;
+// lean implicit gather: chunks per row the per-workgroup tap table holds, and its flag bits
+constexpr int LEAN_MAX_STAGES = 512;
+constexpr uint32_t LEAN_LIVE = 1u, LEAN_TAP_END = 2u;
 
 template <int TN, int WM, int WN>
 struct GemmCfg {
@@ -152,6 +155,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   static_assert(EMODE == 0 || ((WM == 8 || WM == 4) && WN == 1 && (TN == 4 || TN == 2)),
                 "packed epilogue needs 64- or 32-row tiles");
   __shared__ __attribute__((aligned(16))) uint32_t sB[2 * Cfg::TILE];
+  __shared__ uint2 sTab[BMODE == 2 ? 2 * LEAN_MAX_STAGES : 1];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -198,8 +202,8 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   const int rem_bits = p.Kbits - nfull * 32 * KC;
   const int r_words = p.Kw64 - 4 * nfull;                           // words past the full chunks: 0..3
   const bool half = r_words == 2;                                   // finished by one half chunk (4 dwords)
-  const bool window = rem_bits > 0 && !half && p.Kw64 >= 4;         // finished by an overlapping chunk
-  const bool slow_tail = rem_bits > 0 && !half && !window;          // rows of 1 or 3 words only
+  const bool window = BMODE != 2 && rem_bits > 0 && !half && p.Kw64 >= 4;  // finished by an overlapping chunk
+  const bool slow_tail = BMODE != 2 && rem_bits > 0 && !half && !window;   // rows of 1 or 3 words only
   const int nstages = nfull + (rem_bits > 0 ? 1 : 0);
   const int last_w = p.Kw64 - 1;
   const int tail_bits = p.Kbits & 63;
@@ -230,6 +234,54 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
       s_pix0[t] = img * (uint32_t)(p.g.H * p.g.W);
     }
   }
+  // Lean gather (BMODE 2: even Cw, at most 32 taps, image under 4 GiB, at most LEAN_MAX_STAGES
+  // chunks).  Per slot: the byte offset of the pixel under tap (0, 0) (may be "negative": 32-bit
+  // wrap-around arithmetic, only used for taps inside the image) and one validity bit per tap.
+  // Per (chunk, 16-byte piece): an LDS table entry {byte offset of the tap word | flags, tap bit},
+  // built once per workgroup, so the loop holds no division, no geometry and no scalar state for
+  // the gather: a chunk costs a lane one LDS read, one and, one compare, one add, one select.
+  uint32_t f_base[PPT], f_vmask[PPT];
+  bool f_valid[PPT];
+  const int my_piece = tid & 1;  // a thread always stages the same piece of a chunk
+  if constexpr (BMODE == 2) {
+    static_assert(QPR == 2, "two pieces per chunk");
+#pragma unroll
+    for (int t = 0; t < PPT; ++t) {
+      const int idx = t * Cfg::THREADS + tid;
+      const int row = idx / QPR;
+      const uint32_t n = (uint32_t)(n0 + row);
+      const uint32_t wdx = (n >> 8) * 64u + (n & 63u);
+      const bool ok = idx < Cfg::PIECES && (p.g.pool ? wdx < (uint32_t)(p.N >> 2) : n < (uint32_t)p.N);
+      uint32_t img = 0;
+      int oh = 0, ow = 0;
+      if (ok) decode_col(p.g, n, img, oh, ow);
+      const int ih0 = oh * p.g.sH - p.g.pH, iw0 = ow * p.g.sW - p.g.pW;
+      uint32_t colbits = 0, vm = 0;
+#pragma unroll 1
+      for (int kw = 0; kw < p.g.kW; ++kw) colbits |= (uint32_t)(iw0 + kw >= 0 && iw0 + kw < p.g.W) << kw;
+#pragma unroll 1
+      for (int kh = 0; kh < p.g.kH; ++kh)
+        if (ih0 + kh >= 0 && ih0 + kh < p.g.H) vm |= colbits << (kh * p.g.kW);
+      f_vmask[t] = ok ? vm : 0u;  // columns past N read nothing but pad words and are not stored
+      f_base[t] = (uint32_t)((((int64_t)img * p.g.H + ih0) * p.g.W + iw0) * p.g.Cw * 8);
+      f_valid[t] = false;
+    }
+    // entry e = 2 * chunk + piece: words w = 2 e, 2 e + 1 of the row (same tap: Cw is even)
+    const int n_entries = 2 * nstages;
+    for (int e = tid; e < n_entries; e += Cfg::THREADS) {
+      const uint32_t w = 2u * (uint32_t)e;
+      const uint32_t tap = fdiv(w, p.g.divCw);
+      const uint32_t cw = w - tap * (uint32_t)p.g.Cw;
+      const uint32_t kh = fdiv(tap, p.g.divKW);
+      const uint32_t kw = tap - kh * (uint32_t)p.g.kW;
+      const bool live = (int)w <= last_w;  // words past K: no tap, pad word 0
+      uint32_t lo = ((kh * (uint32_t)p.g.W + kw) * (uint32_t)p.g.Cw + cw) * 8u;  // multiple of 16
+      if (live) lo |= LEAN_LIVE;
+      if ((int)cw + 2 == p.g.Cw) lo |= LEAN_TAP_END;
+      sTab[e] = make_uint2(lo, live ? (1u << tap) : 0u);
+    }
+    __syncthreads();
+  }
   // One word of an implicit B row: tap = w / Cw, channel word = w % Cw.
   auto gather_word = [&](int t, int w) -> uint64_t {
     const uint32_t tap = fdiv((uint32_t)w, p.g.divCw);
@@ -247,6 +299,19 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   u32x4 stage[PPT];
   auto stage_load = [&](int s) {
     const int wbase = stage_word0(s);
+    if constexpr (BMODE == 2) {
+      const uint2 ent = sTab[2 * s + my_piece];
+      const uint32_t my_off = ent.x & ~15u;
+      const char *base = reinterpret_cast<const char *>(p.g.act);
+#pragma unroll
+      for (int t = 0; t < PPT; ++t) {
+        const bool valid = (f_vmask[t] & ent.y) != 0u;
+        const uint32_t off = valid ? f_base[t] + my_off : 0u;  // taps outside: any readable address
+        f_valid[t] = valid;
+        stage[t] = *reinterpret_cast<const u32x4 *>(base + off);
+      }
+      return;
+    }
     int tap_cw[2] = {0, 0}, tap_kh[2] = {0, 0}, tap_kw[2] = {0, 0};
     if constexpr (BMODE == 1) {
 #pragma unroll
@@ -310,6 +375,23 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   // past K in the row's last word, then writes the pieces to LDS buffer buf.
   auto stage_store = [&](int buf, int s) {
     const int wbase = stage_word0(s);
+    if constexpr (BMODE == 2) {
+      // pad words: all ones, except the last word of a tap (low C % 64 bits) and words past K (0);
+      // rows hold whole words, so there is no tail mask
+      const uint32_t fl = sTab[2 * s + my_piece].x;
+      const uint64_t last = pad_word64(p.g.C, p.g.Cw - 1);
+      const uint32_t a1 = (fl & LEAN_LIVE) ? 0xffffffffu : 0u;
+      const bool te = (fl & LEAN_TAP_END) != 0u;
+      const u32x4 padv = {a1, a1, te ? (uint32_t)last & a1 : a1, te ? (uint32_t)(last >> 32) & a1 : a1};
+#pragma unroll
+      for (int t = 0; t < PPT; ++t) {
+        const int idx = t * Cfg::THREADS + tid;
+        const int row = idx / QPR, q = idx % QPR;
+        const u32x4 v = f_valid[t] ? stage[t] : padv;
+        if (idx < Cfg::PIECES) *reinterpret_cast<u32x4 *>(&sB[buf * Cfg::TILE + row * RS + q * 4]) = v;
+      }
+      return;
+    }
     const int wdone = (s == nfull && window) ? 4 * nfull : 0;  // words below this are already counted
     const uint32_t tm_lo = (uint32_t)tail_mask, tm_hi = (uint32_t)(tail_mask >> 32);
 #pragma unroll
@@ -672,11 +754,15 @@ static bnn_status launch_cfg(GemmParams &p, int bmode, int emode, hipStream_t s,
   const bool yield = waves >= 2 * 1024;
   if constexpr ((TN == 4 || TN == 2) && (WM == 8 || WM == 4) && WN == 1) {
     if (emode == 1) {
-      if (bmode != 1 || (p.g.pool && TN != 4)) return BNN_ERR_UNSUPPORTED;
+      if (bmode == 0 || (p.g.pool && TN != 4)) return BNN_ERR_UNSUPPORTED;
+      if (bmode == 2)
+        return yield ? launch_one<TN, WM, WN, MINW, 2, 1, 1>(p, s, kid) : launch_one<TN, WM, WN, MINW, 2, 1, 0>(p, s, kid);
       return yield ? launch_one<TN, WM, WN, MINW, 1, 1, 1>(p, s, kid) : launch_one<TN, WM, WN, MINW, 1, 1, 0>(p, s, kid);
     }
   }
   if (emode != 0) return BNN_ERR_UNSUPPORTED;
+  if (bmode == 2)
+    return yield ? launch_one<TN, WM, WN, MINW, 2, 0, 1>(p, s, kid) : launch_one<TN, WM, WN, MINW, 2, 0, 0>(p, s, kid);
   if (bmode == 1)
     return yield ? launch_one<TN, WM, WN, MINW, 1, 0, 1>(p, s, kid) : launch_one<TN, WM, WN, MINW, 1, 0, 0>(p, s, kid);
   return yield ? launch_one<TN, WM, WN, MINW, 0, 0, 1>(p, s, kid) : launch_one<TN, WM, WN, MINW, 0, 0, 0>(p, s, kid);
@@ -699,8 +785,17 @@ static bnn_status launch_direct(GemmParams &p, hipStream_t s) {
   return launch_status();
 }
 
+int g_lean_gather = 1;  // test hook: 0 keeps the general implicit-GEMM gather
+
 bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s) {
   int cfg = g_force_cfg;
+  if (bmode == 1 && g_lean_gather) {
+    // lean gather: 16-byte pieces never straddle a tap (even Cw), one validity bit per tap in a
+    // 32-bit mask, 32-bit byte offsets into the packed image
+    const int64_t taps = (int64_t)p.g.kH * p.g.kW;
+    const int64_t img_bytes = (int64_t)p.g.Nimg * p.g.H * p.g.W * p.g.Cw * 8;
+    if ((p.g.Cw & 1) == 0 && taps <= 32 && img_bytes <= 0xffffffffLL && (p.Kw64 + 3) / 4 <= LEAN_MAX_STAGES) bmode = 2;
+  }
   if (bmode == 0 && emode == 0 && (cfg == 7 || cfg == 8 || cfg < 0)) {
     // Too few 32 x 128 tiles to give every SIMD two waves of the LDS-staged kernel: use
     // independent waves on 8 x 128 (or 8 x 64) tiles instead.
@@ -792,3 +887,4 @@ extern "C" bnn_status bnn_xnor_gemm_epilogue(const uint64_t *A, int64_t lda, con
 
 // Tuning / test hook (not declared in the public header): force a tile configuration.
 extern "C" void bnn_internal_force_gemm_cfg(int cfg) { g_force_cfg = cfg; }
+extern "C" void bnn_internal_lean_gather(int on) { g_lean_gather = on; }

@@ -365,11 +365,17 @@ PACKED_CASES = CONV_CASES + [
     (2, 256, 6, 6, 256, 3, 3, 1, 1, 1, 1),
     (1, 64, 4, 6, 10, 3, 3, 1, 1, 1, 1),
     (1, 320, 16, 16, 70, 3, 3, 1, 1, 1, 1),
+    (2, 100, 7, 9, 33, 3, 3, 1, 1, 1, 1),     # two words per pixel, the second partial
+    (1, 128, 6, 8, 16, 5, 5, 1, 1, 2, 2),     # 25 taps
+    (1, 128, 10, 10, 8, 6, 6, 1, 1, 2, 2),    # 36 taps: more than the tap mask of the lean gather holds
+    (2, 128, 9, 9, 20, 3, 3, 2, 2, 1, 1),     # stride 2
+    (2, 128, 6, 6, 12, 1, 1, 1, 1, 0, 0),     # rows of two words: a half chunk only
+    (2, 192, 6, 6, 12, 1, 1, 1, 1, 0, 0),     # rows of three words (odd: general gather)
 ]
 
 
 @pytest.mark.parametrize("cfg", [1, 3, 4, 6])
-@pytest.mark.parametrize("case", PACKED_CASES[-5:] + PACKED_CASES[1:4])
+@pytest.mark.parametrize("case", PACKED_CASES[-11:] + PACKED_CASES[1:4])
 def test_conv2d_packed_forced_tiles(case, cfg):
     """The binarizing epilogue on every tile shape it is written for (the pooled form only
     exists for the four-column tiles; other requests fall back to a legal tile)."""
@@ -395,9 +401,19 @@ def test_conv2d_packed_forced_tiles(case, cfg):
         B.lib().bnn_internal_force_gemm_cfg(-1)
 
 
+@pytest.mark.parametrize("lean", [1, 0])
 @pytest.mark.parametrize("case", PACKED_CASES)
-def test_conv2d_packed_all_output_kinds(case):
-    print(f"conv2d_packed case={case}", flush=True)
+def test_conv2d_packed_all_output_kinds(case, lean):
+    """lean = 0 forces the general implicit-GEMM gather also where the lean one applies."""
+    print(f"conv2d_packed case={case} lean={lean}", flush=True)
+    B.lib().bnn_internal_lean_gather(lean)
+    try:
+        _conv2d_packed_all_output_kinds(case)
+    finally:
+        B.lib().bnn_internal_lean_gather(1)
+
+
+def _conv2d_packed_all_output_kinds(case):
     N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
     shape = inputs.ConvShape(*case)
     d = inputs.conv_inputs(shape, seed=sum(case) + 2)
