@@ -173,15 +173,20 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   const int m0 = mi * Cfg::BM + wm * TM;
   const int n0 = ni * Cfg::BN;
 
-  // Byte offsets of this wave's TM rows (clamped: rows past M recompute row M-1 and are
-  // not stored), held in SGPRs.  32-bit: the host checks that M * lda32 * 4 < 2^32.
-  uint32_t aoffb[TM];
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    int m = m0 + i;
-    m = m < p.M ? m : p.M - 1;
-    aoffb[i] = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)m * (uint32_t)p.lda32 * 4u));
+  // Byte offsets of this wave's TM rows: first row + i * row bytes, clamped to the last row of A
+  // (rows past M recompute row M-1 and are not stored).  Three SGPRs; the eight offsets are
+  // recomputed on the scalar unit every chunk instead of living in (spilled) registers.
+  // 32-bit: the host checks that M * lda32 * 4 < 2^32.
+  const uint32_t arow_bytes = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)p.lda32 * 4u));
+  const uint32_t aoff_max = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(p.M - 1) * (uint32_t)p.lda32 * 4u));
+  uint32_t aoff_first;
+  {
+    const int mf = m0 < p.M ? m0 : p.M - 1;
+    aoff_first = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)mf * (uint32_t)p.lda32 * 4u));
   }
+  // Re-defining the first offset through an empty asm inside the loop keeps the compiler from
+  // hoisting the eight derived offsets out of it.
+#define BNN_AOFF(i) min(aoff_cur + (uint32_t)(i) * arow_bytes, aoff_max)
   // 64-bit base of A in an SGPR pair (readfirstlane returns a signed int: each half is cast
   // to unsigned before widening).
   const uint32_t Abase_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)p.A);
@@ -433,9 +438,11 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
     const uint64_t Abase = Abase0 + (uint64_t)(uint32_t)stage_word0(c) * 8u;
     u32x8 a[TM];
     u32x8 b[TN];
+    uint32_t aoff_cur = aoff_first;
+    asm volatile("" : "+s"(aoff_cur));
 #pragma unroll
     for (int i = 0; i < TM; ++i)
-      asm volatile("s_load_dwordx8 %0, %1, %2" : "=s"(a[i]) : "s"(Abase), "s"(aoffb[i]));
+      asm volatile("s_load_dwordx8 %0, %1, %2" : "=s"(a[i]) : "s"(Abase), "s"(BNN_AOFF(i)));
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       b[j].lo = *reinterpret_cast<const u32x4 *>(&sBl[j * 64 * RS]);
@@ -445,7 +452,8 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
                  : "+s"(a[0]), "+s"(a[1]), "+s"(a[2]), "+s"(a[3]), "+s"(a[4]), "+s"(a[5]), "+s"(a[6]), "+s"(a[7]));
     if (is_window) {
       // dwords already counted by the full chunks, and the bits past K, leave A as zeros
-      const int dw_done = 2 * (4 * nfull - (p.Kw64 - 4));
+      int dw_done = 2 * (4 * nfull - (p.Kw64 - 4));
+      asm volatile("" : "+s"(dw_done));  // the eight compares below stay here, not in registers across the loop
       const uint32_t m6 = (uint32_t)tail_mask, m7 = (uint32_t)(tail_mask >> 32);
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
@@ -485,9 +493,11 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
     const uint64_t Abase = Abase0 + (uint64_t)(uint32_t)(4 * nfull) * 8u;
     u32x4 a[TM];
     u32x4 b[TN];
+    uint32_t aoff_cur = aoff_first;
+    asm volatile("" : "+s"(aoff_cur));
 #pragma unroll
     for (int i = 0; i < TM; ++i)
-      asm volatile("s_load_dwordx4 %0, %1, %2" : "=s"(a[i]) : "s"(Abase), "s"(aoffb[i]));
+      asm volatile("s_load_dwordx4 %0, %1, %2" : "=s"(a[i]) : "s"(Abase), "s"(BNN_AOFF(i)));
 #pragma unroll
     for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const u32x4 *>(&sBl[j * 64 * RS]);
     asm volatile("s_waitcnt lgkmcnt(0)"
@@ -529,9 +539,11 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
       uint32_t b[TN];
 #pragma unroll
       for (int j = 0; j < TN; ++j) b[j] = sBl[j * 64 * RS + (kd - kd0)];
+      uint32_t aoff_cur = aoff_first;
+      asm volatile("" : "+s"(aoff_cur));
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        const uint32_t a = Ac[(aoffb[i] >> 2) + kd] & amask;
+        const uint32_t a = Ac[(BNN_AOFF(i) >> 2) + kd] & amask;
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = popc_acc(a ^ b[j], acc[i][j]);
       }
@@ -556,22 +568,25 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
     uint32_t bytes[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) bytes[j] = 0u;
+    // Rows run from the last to the first so that each sign is shifted in with one add-with-carry
+    // (byte = 2 * byte + bit).  K - 2*acc decreases in acc: the 2x2 max is K - 2*min(acc).
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int i = TM - 1; i >= 0; --i) {
       const int m = m0 + i;
       const bool row_ok = m < M;
       const float sc = row_ok ? scale[m] : 0.0f;
       const float bi = row_ok ? bias[m] : -1.0f;  // rows past M give bit 0
       if (pool) {
-        int v = Kformula - 2 * acc[i][0];
+        int a = acc[i][0];
 #pragma unroll
-        for (int j = 1; j < TN; ++j) v = max(v, Kformula - 2 * acc[i][j]);
-        bytes[0] |= (uint32_t)(fmaf(sc, (float)v, bi) >= 0.0f) << i;
+        for (int j = 1; j < TN; ++j) a = min(a, acc[i][j]);
+        const float y = fmaf(sc, (float)(Kformula - 2 * a), bi);
+        asm("v_cmp_le_f32 vcc, 0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(bytes[0]) : "v"(y) : "vcc");
       } else {
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          const int v = Kformula - 2 * acc[i][j];
-          bytes[j] |= (uint32_t)(fmaf(sc, (float)v, bi) >= 0.0f) << i;
+          const float y = fmaf(sc, (float)(Kformula - 2 * acc[i][j]), bi);
+          asm("v_cmp_le_f32 vcc, 0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(bytes[j]) : "v"(y) : "vcc");
         }
       }
     }
