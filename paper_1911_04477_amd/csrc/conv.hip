@@ -136,7 +136,8 @@ __global__ __launch_bounds__(256) void conv2d_f32_sign_kernel(const float *__res
   }
 }
 
-// 3x3x3 specialization (K = 27).  Each lane owns F32S_NP output pixels (p + q * part), so one
+// 3x3x3 specialization (K = 27).  A workgroup computes 64 output channels (one stored word) of
+// its pixels; each lane owns F32S_NP output pixels (p + q * part), so one
 // set of scalar weight loads feeds 27 * F32S_NP fused multiply-adds, and the loads of the next channel
 // (27 weights, scale, bias: 29 SGPRs) are issued before the current channel is computed: the
 // scalar-memory latency is covered by compute instead of being waited for per channel.
@@ -249,16 +250,17 @@ __global__ __launch_bounds__(256) void conv2d_f32_sign27_kernel(const float *__r
       }
     }
   };
-  const int Dpad = cw_out * 64;
+  // blockIdx.y selects the 64 output channels (one stored word per pixel) this workgroup computes
+  const int ch_lo = 64 * (int)blockIdx.y, ch_hi = ch_lo + 63;
   const int last = D - 1;
   F32sWSet SA, SB;
-  F32S_LOAD(SA, (Dpad - 1 < last ? Dpad - 1 : last));
-  for (int ch = Dpad - 1; ch > 0; ch -= 2) {
+  F32S_LOAD(SA, (ch_hi < last ? ch_hi : last));
+  for (int ch = ch_hi; ch > ch_lo; ch -= 2) {
     F32S_WAIT(SA);
     F32S_LOAD(SB, (ch - 1 < last ? ch - 1 : last));
     compute(SA, ch);
     F32S_WAIT(SB);
-    if (ch >= 2) F32S_LOAD(SA, (ch - 2 < last ? ch - 2 : last));
+    if (ch - 2 >= ch_lo) F32S_LOAD(SA, (ch - 2 < last ? ch - 2 : last));
     compute(SB, ch - 1);
   }
 }
@@ -361,7 +363,7 @@ extern "C" bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N,
     const dim3 block(256);
     if (K == 27 && C == 3 && kH == 3 && kW == 3) {
       const int64_t part = (total + F32S_NP - 1) / F32S_NP;
-      const dim3 grid((unsigned)((part + 255) / 256));
+      const dim3 grid((unsigned)((part + 255) / 256), (unsigned)bnn_packed_words(D));
       hipLaunchKernelGGL(conv2d_f32_sign27_kernel, grid, block, 0, s, x, w, H, W, D, sH, sW, pH, pW, (int)OH, (int)OW,
                          scale, bias, out_packed, (int)bnn_packed_words(D), FastDiv((uint32_t)OW),
                          FastDiv((uint32_t)OH), (uint32_t)total, (uint32_t)part);

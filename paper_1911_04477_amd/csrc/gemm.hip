@@ -626,11 +626,15 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
 // bound by its per-chunk latency chain (global load -> LDS -> barrier).  Here every lane reads
 // its own columns' words straight from global memory into registers, DEPTH chunks ahead, and
 // the wave never synchronises with anyone.  A is fetched with scalar loads as above.
-template <int TN, int DEPTH, int YIELD>
+// KS = 4: the four waves of a workgroup share ONE tile and split its K range (problems with
+// fewer tiles than SIMDs but long rows); their partial counts are summed through LDS.
+template <int TN, int DEPTH, int YIELD, int KS>
 __global__ __launch_bounds__(256) void xnor_gemm_direct_kernel(GemmParams p) {
+  static_assert(KS == 1 || KS == 4, "one tile per wave, or one per workgroup");
+  __shared__ int sRed[KS == 4 ? 3 * TM * TN * 64 : 1];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  const uint32_t wid = blockIdx.x * 4u + (uint32_t)wave;  // tile index, M fastest
+  const uint32_t wid = KS == 4 ? blockIdx.x : blockIdx.x * 4u + (uint32_t)wave;  // tile index, M fastest
   const int mi = (int)(wid % (uint32_t)p.tilesM);
   const int ni = (int)(wid / (uint32_t)p.tilesM);
   if (ni >= p.tilesN) return;
@@ -664,8 +668,13 @@ __global__ __launch_bounds__(256) void xnor_gemm_direct_kernel(GemmParams p) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) acc[i][j] = 0;
 
-  const int nfull = p.Kbits / (32 * KC);
-  auto load_b = [&](u32x8 (&b)[TN], int c) {
+  const int nfull_all = p.Kbits / (32 * KC);
+  // this wave's range of full chunks: [cb, cb + nfull)
+  const int per = KS == 4 ? (nfull_all + 3) / 4 : nfull_all;
+  const int cb = KS == 4 ? min(wave * per, nfull_all) : 0;
+  const int nfull = KS == 4 ? min(per, nfull_all - cb) : nfull_all;
+  auto load_b = [&](u32x8 (&b)[TN], int cl) {
+    const int c = cb + cl;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const uint64_t *src = brow[j] + 4 * c;
@@ -682,8 +691,8 @@ __global__ __launch_bounds__(256) void xnor_gemm_direct_kernel(GemmParams p) {
       }
     }
   };
-  auto compute = [&](u32x8 (&b)[TN], int c) {
-    const uint64_t Abase = Abase0 + (uint64_t)(uint32_t)c * 32u;
+  auto compute = [&](u32x8 (&b)[TN], int cl) {
+    const uint64_t Abase = Abase0 + (uint64_t)(uint32_t)(cb + cl) * 32u;
     u32x8 a[TM];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -722,9 +731,10 @@ __global__ __launch_bounds__(256) void xnor_gemm_direct_kernel(GemmParams p) {
   for (int d = 0; d < DEPTH; ++d)
     if (c + d < nfull) compute(bq[d], c + d);
 
-  // bits past the last full chunk: one dword at a time, both operands masked
-  {
-    const int kd0 = nfull * KC;
+  // bits past the last full chunk: one dword at a time, both operands masked (first wave only
+  // when the K range is split)
+  if (KS == 1 || wave == 0) {
+    const int kd0 = nfull_all * KC;
     const int tb32 = p.Kbits & 31;
     const uint32_t *b32[TN];
 #pragma unroll
@@ -742,6 +752,23 @@ __global__ __launch_bounds__(256) void xnor_gemm_direct_kernel(GemmParams p) {
         for (int j = 0; j < TN; ++j) acc[i][j] = popc_acc(a ^ b[j], acc[i][j]);
       }
     }
+  }
+  if constexpr (KS == 4) {
+    // every wave of the workgroup is here (the early return above is per workgroup)
+    if (wave > 0) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) sRed[((wave - 1) * TM * TN + i * TN + j) * 64 + lane] = acc[i][j];
+    }
+    __syncthreads();
+    if (wave > 0) return;
+#pragma unroll
+    for (int w = 0; w < 3; ++w)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] += sRed[(w * TM * TN + i * TN + j) * 64 + lane];
   }
   store_tile<TN>(acc, m0, nbase);
 }
@@ -786,17 +813,27 @@ static bnn_status launch_cfg(GemmParams &p, int bmode, int emode, hipStream_t s,
 int g_force_cfg = -1;  // test / tuning hook: -1 = heuristic
 
 template <int TN>
-static bnn_status launch_direct(GemmParams &p, hipStream_t s) {
+static bnn_status launch_direct(GemmParams &p, hipStream_t s, int ksplit = -1) {  // ksplit: -1 heuristic, 0 off, 1 on
   p.tilesM = (p.M + TM - 1) / TM;
   p.tilesN = (p.N + 64 * TN - 1) / (64 * TN);
   const int64_t waves = (int64_t)p.tilesM * p.tilesN;
-  const int64_t blocks = (waves + 3) / 4;
-  if (blocks > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+  if (waves > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   ProfScope ps(KID_XNOR_GEMM_SMALL, s);
+  if constexpr (TN == 1) {
+    // fewer tiles than SIMDs and at least four chunks per wave after the split: four waves per tile
+    if (ksplit > 0 || (ksplit < 0 && waves < 1024 && p.Kbits / (32 * KC) >= 16)) {
+      if (4 * waves >= 2 * 1024)
+        hipLaunchKernelGGL((xnor_gemm_direct_kernel<1, 4, 1, 4>), dim3((unsigned)waves), dim3(256), 0, s, p);
+      else
+        hipLaunchKernelGGL((xnor_gemm_direct_kernel<1, 4, 0, 4>), dim3((unsigned)waves), dim3(256), 0, s, p);
+      return launch_status();
+    }
+  }
+  const int64_t blocks = (waves + 3) / 4;
   if (waves >= 2 * 1024)
-    hipLaunchKernelGGL((xnor_gemm_direct_kernel<TN, 4, 1>), dim3((unsigned)blocks), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((xnor_gemm_direct_kernel<TN, 4, 1, 1>), dim3((unsigned)blocks), dim3(256), 0, s, p);
   else
-    hipLaunchKernelGGL((xnor_gemm_direct_kernel<TN, 4, 0>), dim3((unsigned)blocks), dim3(256), 0, s, p);
+    hipLaunchKernelGGL((xnor_gemm_direct_kernel<TN, 4, 0, 1>), dim3((unsigned)blocks), dim3(256), 0, s, p);
   return launch_status();
 }
 
@@ -817,8 +854,9 @@ bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s) {
     const int64_t t32 = (int64_t)((p.M + 31) / 32) * ((p.N + 127) / 128);
     const int64_t w128 = (int64_t)((p.M + 7) / 8) * ((p.N + 127) / 128);
     if (cfg == 8 || (cfg < 0 && t32 < 512 && w128 >= 2048)) return launch_direct<2>(p, s);
-    if (cfg == 7 || (cfg < 0 && t32 < 512)) return launch_direct<1>(p, s);
+    if (cfg == 7 || (cfg < 0 && t32 < 512)) return launch_direct<1>(p, s, cfg == 7 ? 0 : -1);
   }
+  if (bmode == 0 && emode == 0 && cfg == 9) return launch_direct<1>(p, s, 1);  // forced K split
   if (emode == 1) {
     // tiles the packed epilogue is written for: 64 x 256 (3), 64 x 128 (6), 32 x 256 (1), 32 x 128 (4);
     // pooling needs four columns per lane (3 or 1)

@@ -144,6 +144,22 @@ __global__ __launch_bounds__(256) void fc_f32_kernel(const float *__restrict__ x
     __syncthreads();
     const float *px = &sx[r * FC_RS], *pw = &sw[j * FC_RS];
     int kk = 0;
+    // 32 k per round: all sixteen 16-byte LDS reads are issued before the chain consumes them
+    for (; kk + 32 <= kc; kk += 32) {
+      float4 a[8], b[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        a[u] = *reinterpret_cast<const float4 *>(px + kk + 4 * u);
+        b[u] = *reinterpret_cast<const float4 *>(pw + kk + 4 * u);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        acc = fmaf(a[u].x, b[u].x, acc);
+        acc = fmaf(a[u].y, b[u].y, acc);
+        acc = fmaf(a[u].z, b[u].z, acc);
+        acc = fmaf(a[u].w, b[u].w, acc);
+      }
+    }
     for (; kk + 4 <= kc; kk += 4) {
       const float4 a = *reinterpret_cast<const float4 *>(px + kk);
       const float4 b = *reinterpret_cast<const float4 *>(pw + kk);

@@ -104,7 +104,7 @@ def _gemm_case(M, N, K, seed, cfg=None):
 
 
 @pytest.mark.parametrize("K", [1, 31, 32, 33, 63, 64, 65, 200, 256, 257, 511, 512, 544, 1152, 2304 + 17])
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 6, 7, 8])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 6, 7, 8, 9])
 def test_gemm_k_sweep_all_tile_configs(K, cfg):
     print(f"gemm K={K} cfg={cfg}", flush=True)
     B.lib().bnn_internal_force_gemm_cfg(cfg)
@@ -115,7 +115,7 @@ def test_gemm_k_sweep_all_tile_configs(K, cfg):
 
 
 @pytest.mark.parametrize("M,N", [(1, 1), (1, 700), (65, 513), (64, 512), (130, 1030), (257, 64), (33, 65)])
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 6, 7, 8])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 6, 7, 8, 9])
 def test_gemm_ragged_tiles(M, N, cfg):
     print(f"gemm M={M} N={N} cfg={cfg}", flush=True)
     B.lib().bnn_internal_force_gemm_cfg(cfg)
