@@ -135,3 +135,19 @@ class VggStackFused:
             if keep:
                 acts.append(h.clone())
         return (h, acts) if keep else h
+
+    def conv_launches(self):
+        """One closure per binarized convolution that re-issues exactly that layer's launch on the
+        buffers the last forward() left behind (for timing a launch in isolation)."""
+        out = []
+        prev = None
+        for L, p, b in zip(self.layers, self.p, self.buf):
+            if L.kind == "bconv":
+                src = prev
+
+                def call(L=L, p=p, b=b, src=src):
+                    B.bnn_conv2d_packed(src, p["wp"], L.cin, L.cout, 3, 3, (1, 1), (1, 1), pool=2 if L.pool else 0,
+                                        scale=p["scale"], bias=p["bias"], out="packed", out_buf=b["yp"])
+                out.append(call)
+            prev = b.get("yp", None)
+        return out
