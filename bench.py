@@ -315,6 +315,36 @@ def mfma_ablation():
     return out
 
 
+def control_group():
+    """The paper's float control group on this machine: the same convolution as an fp32 MFMA GEMM on
+    sign(x), sign(w) (implicit GEMM, no patch matrix) beside the Xnor-Bitcount path (bnn_conv2d)."""
+    import torch
+    from paper_1911_04477_amd import binding as B
+    from paper_1911_04477_amd import inputs
+    dev = "cuda:0"
+    out = {}
+    for name, shape in (("cfg3", inputs.CFG3), ("cfg5a", inputs.CFG5A)):
+        x = torch.randn((shape.N, shape.C, shape.H, shape.W), device=dev)
+        w = torch.randn((shape.D, shape.C, shape.kH, shape.kW), device=dev)
+        st, pd = (shape.sH, shape.sW), (shape.pH, shape.pW)
+        yf = torch.empty((shape.N, shape.D, shape.OH, shape.OW), dtype=torch.float32, device=dev)
+        yi = torch.empty((shape.N, shape.D, shape.OH, shape.OW), dtype=torch.int32, device=dev)
+        wp = B.bnn_pack_conv_weight(w)
+        ws = torch.empty(B.conv2d_workspace_bytes(x.shape, shape.kH, shape.kW, st, pd), dtype=torch.uint8, device=dev)
+        tc, _ = time_steps(lambda: B.bnn_control_conv2d_f32(x, w, st, pd, yf), 30, 10)
+        tb, _ = time_steps(lambda: B.bnn_conv2d(x, wp, shape.D, shape.kH, shape.kW, st, pd, want_int=True, workspace=ws,
+                                               out_i32=yi), 300, 100)
+        tc, tb = tc / 30, tb / 300
+        flops = 2.0 * shape.bit_macs
+        out[name] = {"control_fp32_ms": round(tc * 1e3, 4), "control_TFLOPs": round(flops / tc / 1e12, 1),
+                     "control_frac_of_fp32_mfma_peak": round(flops / tc / 157.3e12, 4),
+                     "xnor_ms": round(tb * 1e3, 4), "speedup": round(tc / tb, 2),
+                     "speedup_vs_fp32_mfma_peak": round(flops / 157.3e12 / tb, 2),
+                     "same_result": bool((yf == yi.to(torch.float32)).all().item())}
+        del x, w, yf, yi, ws
+    return out
+
+
 def other_configs(args):
     out = {}
     for name in ("cfg2", "cfg3", "cfg5a", "cfg5b"):
@@ -413,6 +443,7 @@ def main():
         line["hbm_peak_GBs"] = HBM_PEAK_GBS
         line["other_configs"] = other_configs(args)
         line["mfma_ablation"] = mfma_ablation()
+        line["control_group"] = control_group()
     print(json.dumps(line), flush=True)
 
 

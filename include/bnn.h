@@ -238,6 +238,22 @@ bnn_status bnn_xnor_gemm_mfma_i8(const uint64_t *A, int64_t lda, const uint64_t 
                                  int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K,
                                  void *stream);
 
+/* ---- control group --------------------------------------------------------------------- */
+
+/*
+ * bnn_control_conv2d_f32 -- the paper's fp32 "control group" (section 4.4): the same
+ * binarized convolution computed as an ordinary real-valued GEMM, for restating the kernel's
+ * speed-up on this machine.  out[n, d, oh, ow] = sum over (c, kh, kw) of sign(w) * sign(x),
+ * taps outside the image counting as sign(0) = +1; every value is an exact integer in fp32
+ * and equals bnn_conv2d's int32 result.  Implicit GEMM on the fp32 matrix cores, no workspace.
+ *   x   [N, C, H, W] fp32 (device), w [D, C, kH, kW] fp32 (device), out [N, D, OH, OW] fp32
+ *   (device, written).  All three 16-byte aligned.  C*kH*kW < 2^24.
+ * Errors as bnn_conv2d.  Not used by any other entry point.
+ */
+bnn_status bnn_control_conv2d_f32(const float *x, const float *w, int N, int C, int H, int W,
+                                  int D, int kH, int kW, int sH, int sW, int pH, int pW,
+                                  float *out, void *stream);
+
 /* ---- measurement helpers ------------------------------------------------------------ */
 
 /*

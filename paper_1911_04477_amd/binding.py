@@ -31,6 +31,7 @@ SIGNATURES = {
     "bnn_im2col_workspace_bytes": (_sz, [_i32] * 10),
     "bnn_xnor_gemm": (_i32, [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _p]),
     "bnn_xnor_gemm_mfma_i8": (_i32, [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _p]),
+    "bnn_control_conv2d_f32": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p]),
     "bnn_xnor_gemm_epilogue": (_i32, [_p, _i64, _p, _i64, _i64, _i64, _i64, _p, _i64, _p, _i64, _p, _p, _i32, _p]),
     "bnn_conv2d": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p, _p, _p, _p, _sz, _p]),
     "bnn_conv2d_workspace_bytes": (_sz, [_i32] * 10),
@@ -173,6 +174,21 @@ def bnn_xnor_gemm_mfma_i8(A: torch.Tensor, B: torch.Tensor, K: int, C: Optional[
     _check(lib().bnn_xnor_gemm_mfma_i8(_ptr(A), lda, _ptr(B), ldb, _ptr(C), C.stride(0) if M > 1 else max(N, 1), M, N,
                                        K, _stream()), "bnn_xnor_gemm_mfma_i8")
     return C
+
+
+def bnn_control_conv2d_f32(x: torch.Tensor, w: torch.Tensor, stride=(1, 1), pad=(0, 0),
+                           out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Control group: the binarized convolution as an fp32 GEMM on sign(x), sign(w)."""
+    _dev(x, torch.float32, "x")
+    _dev(w, torch.float32, "w")
+    N, C, H, W = x.shape
+    D, _, kH, kW = w.shape
+    OH, OW = conv_out_dim(H, kH, stride[0], pad[0]), conv_out_dim(W, kW, stride[1], pad[1])
+    if out is None:
+        out = torch.empty((N, D, OH, OW), dtype=torch.float32, device=x.device)
+    _check(lib().bnn_control_conv2d_f32(_ptr(x), _ptr(w), N, C, H, W, D, kH, kW, stride[0], stride[1], pad[0], pad[1],
+                                        _ptr(out), _stream()), "bnn_control_conv2d_f32")
+    return out
 
 
 def bnn_xnor_gemm_epilogue(A: torch.Tensor, B: torch.Tensor, K: int, scale: torch.Tensor, bias: torch.Tensor,

@@ -22,7 +22,8 @@ enum KernelId : int {
   KID_XNOR_GEMM_SMALL = 10,
   KID_CONV_F32_SIGN = 11,
   KID_XNOR_GEMM_MFMA = 12,
-  KID_COUNT = 13
+  KID_CONTROL_CONV_F32 = 13,
+  KID_COUNT = 14
 };
 
 // Timing hook: records an event pair around a launch when profiling is on.

@@ -510,3 +510,27 @@ def test_mfma_ablation_equals_valu_path_at_cfg2():
     a = host(B.bnn_xnor_gemm_mfma_i8(Ap, Wp, inputs.CFG2.K))
     b = host(B.bnn_xnor_gemm(Ap, Wp, inputs.CFG2.K))
     assert np.array_equal(a, b)
+
+
+# ---------------------------------------------------------------- fp32 control group (section 4.4)
+@pytest.mark.parametrize("case", PACKED_CASES + [(1, 3, 5, 5, 130, 3, 3, 1, 1, 1, 1), (2, 40, 20, 20, 200, 3, 3, 2, 2, 0, 0)])
+def test_control_group_conv_equals_binarized_result(case):
+    """The real-valued GEMM on sign(x), sign(w) gives the same integers as the oracle (and so as
+    the Xnor-Bitcount path), exactly: all partial sums are integers below 2^24."""
+    print(f"control conv case={case}", flush=True)
+    N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
+    shape = inputs.ConvShape(*case)
+    d = inputs.conv_inputs(shape, seed=sum(case) + 5)
+    x = inputs.inject_specials(d["x"], 6, frac=0.01)
+    got = host(B.bnn_control_conv2d_f32(dev(x), dev(d["w"]), (sH, sW), (pH, pW)))
+    ref = oracle.conv2d_pm1(x, d["w"], (sH, sW), (pH, pW))
+    assert got.dtype == np.float32 and np.array_equal(got, ref.astype(np.float32))
+
+
+def test_control_group_conv_cfg3_full_size():
+    print("control conv cfg3", flush=True)
+    d = inputs.cfg3()
+    s = inputs.CFG3
+    got = host(B.bnn_control_conv2d_f32(dev(d["x"]), dev(d["w"]), (s.sH, s.sW), (s.pH, s.pW)))
+    ref = oracle.conv2d_pm1(d["x"], d["w"], (s.sH, s.sW), (s.pH, s.pW))
+    assert np.array_equal(got, ref.astype(np.float32))
