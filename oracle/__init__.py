@@ -80,6 +80,9 @@ def gemm_pm1(A, B) -> np.ndarray:
     (section 3.2, Gemm-Accumulation on binary values)."""
     A, B = _f32(A), _f32(B)
     assert A.ndim == 2 and B.ndim == 2 and A.shape[1] == B.shape[1]
+    # the sum of K terms +-1 is accumulated in fp32, which holds every integer only below 2^24
+    if A.shape[1] >= 1 << 24:
+        raise ValueError("gemm_pm1: K >= 2^24 is outside the range in which the fp32 sum is exact")
     C = np.empty((A.shape[0], B.shape[0]), dtype=np.int32)
     lib().oracle_gemm_pm1(_ptr(A), _ptr(B), A.shape[0], B.shape[0], A.shape[1], _ptr(C))
     return C
@@ -93,6 +96,8 @@ def conv2d_pm1(x, w, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
     """Direct convolution of section 2.1 on binary values; x NCHW fp32, w [D,C,kH,kW]
     fp32, zero padding applied before the sign (pad taps are +1) -> int32 NCHW."""
     x, w = _f32(x), _f32(w)
+    if w[0].size >= 1 << 24:
+        raise ValueError("conv2d_pm1: C*kH*kW >= 2^24 is outside the range in which the fp32 sum is exact")
     N, C, H, W = x.shape
     D, C2, kH, kW = w.shape
     assert C == C2
@@ -106,6 +111,8 @@ def conv2d_pm1(x, w, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
 def conv2d_pm1_at(x, w, flat_idx, stride=(1, 1), pad=(0, 0)) -> np.ndarray:
     """conv2d_pm1 evaluated only at the given flat indices of the NCHW output."""
     x, w = _f32(x), _f32(w)
+    if w[0].size >= 1 << 24:
+        raise ValueError("conv2d_pm1: C*kH*kW >= 2^24 is outside the range in which the fp32 sum is exact")
     N, C, H, W = x.shape
     D, C2, kH, kW = w.shape
     assert C == C2

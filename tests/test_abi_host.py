@@ -187,6 +187,36 @@ def test_glue_errors(L):
     assert L.bnn_copy_probe(A16, None, 32, None) == NULL
 
 
+def test_ablation_and_control_errors(L):
+    mf = L.bnn_xnor_gemm_mfma_i8
+    assert mf(A16, 4, A16, 4, A16, 8, 8, 8, 0, None) == SHAPE          # K = 0
+    assert mf(A16, 1, A16, 4, A16, 8, 8, 8, 200, None) == STRIDE       # lda < words
+    assert mf(A16, 4, A16, 4, A16, 4, 8, 8, 200, None) == STRIDE       # ldc < N
+    assert mf(A16, 4, A16, 4, None, 8, 8, 8, 200, None) == NULL
+    assert mf(A16, 4, MIS, 4, A16, 8, 8, 8, 200, None) == ALIGN
+    assert mf(None, 4, None, 4, None, 8, 0, 8, 200, None) == OK        # empty problem: nothing touched
+    cc = L.bnn_control_conv2d_f32
+    assert cc(A16, A16, 2, 3, 8, 8, 4, 9, 9, 1, 1, 0, 0, A16, None) == SHAPE   # kernel larger than image
+    assert cc(A16, A16, 2, 3, 8, 8, -1, 3, 3, 1, 1, 1, 1, A16, None) == SHAPE
+    assert cc(A16, None, 2, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1, A16, None) == NULL
+    assert cc(A16, A16, 2, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1, MIS, None) == ALIGN
+    assert cc(None, None, 0, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1, None, None) == OK   # empty batch
+
+
+def test_empty_problems_succeed_without_touching_anything(L):
+    """Zero rows / columns / images / channels return OK before any pointer is looked at."""
+    assert L.bnn_encode(None, 0, 64, 64, None, 1, None) == OK
+    assert L.bnn_pack_conv_weight(None, 0, 3, 3, 3, None, None) == OK
+    assert L.bnn_xnor_gemm(None, 4, None, 4, None, 8, 0, 8, 200, None) == OK
+    assert L.bnn_xnor_gemm(None, 4, None, 4, None, 0, 8, 0, 200, None) == OK
+    assert L.bnn_xnor_gemm_epilogue(None, 4, None, 4, 0, 8, 200, None, 8, None, 8, None, None, 1, None) == OK
+    assert L.bnn_conv2d(None, None, 0, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1, None, None, None, None, None, 0, None) == OK
+    assert L.bnn_conv2d(None, None, 2, 3, 8, 8, 0, 3, 3, 1, 1, 1, 1, None, None, None, None, None, 0, None) == OK
+    assert L.bnn_conv2d_f32_sign(None, None, 0, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1, None, None, None, None) == OK
+    assert L.bnn_pack_fc_weight_nhwc(None, 0, 4, 2, 2, None, None) == OK
+    assert L.bnn_fc_f32(None, None, None, 0, 8, 4, 0, None, None) == OK
+
+
 def test_prof_hook_is_inert_without_launches(L):
     assert L.bnn_prof_count() == 0
     assert L.bnn_prof_reset() == OK

@@ -534,3 +534,51 @@ def test_control_group_conv_cfg3_full_size():
     got = host(B.bnn_control_conv2d_f32(dev(d["x"]), dev(d["w"]), (s.sH, s.sW), (s.pH, s.pW)))
     ref = oracle.conv2d_pm1(d["x"], d["w"], (s.sH, s.sW), (s.pH, s.pW))
     assert np.array_equal(got, ref.astype(np.float32))
+
+
+# ---------------------------------------------------------------- sizes far off the tile grid
+def _popcount_rows(a_words, b_words, K):
+    """K - 2 * popcount(a xor b) for every pair of packed rows, with numpy only: the identity the
+    oracle's float GEMM is pinned against, usable where K >= 2^24 puts that fp32 sum out of its
+    exact range."""
+    x = a_words[:, None, :] ^ b_words[None, :, :]
+    cnt = np.unpackbits(x.view(np.uint8), axis=-1).sum(axis=-1, dtype=np.int64)
+    return (K - 2 * cnt).astype(np.int32)
+
+
+@pytest.mark.parametrize("cfg", [-1, 3, 7, 9])
+def test_gemm_very_long_rows(cfg):
+    """K = 2^24 + 77 bits: 65536 full chunks and a ragged tail per row, accumulators in the millions."""
+    print(f"gemm long K cfg={cfg}", flush=True)
+    M, N, K = 3, 5, (1 << 24) + 77
+    rng = np.random.default_rng(77)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    Bm = rng.standard_normal((N, K)).astype(np.float32)
+    Bm[1] = A[0]            # one identical pair: C = K
+    Bm[2] = -A[1]           # one opposite pair: C = -K (no zeros in a normal sample)
+    Ap, Bp = B.bnn_encode(dev(A)), B.bnn_encode(dev(Bm))
+    B.lib().bnn_internal_force_gemm_cfg(cfg)
+    try:
+        got = host(B.bnn_xnor_gemm(Ap, Bp, K))
+    finally:
+        B.lib().bnn_internal_force_gemm_cfg(-1)
+    assert got[0, 1] == K and got[1, 2] == -K
+    # rows encoded by the oracle, not by the GPU
+    assert np.array_equal(got, _popcount_rows(oracle.encode_rows(A), oracle.encode_rows(Bm), K))
+    # the first 2^24 - 1 columns through the float oracle, the rest by the identity
+    K0 = (1 << 24) - 1
+    head = oracle.gemm_pm1(np.ascontiguousarray(A[:, :K0]), np.ascontiguousarray(Bm[:, :K0]))
+    tail = _popcount_rows(oracle.encode_rows(np.ascontiguousarray(A[:, K0:])),
+                          oracle.encode_rows(np.ascontiguousarray(Bm[:, K0:])), K - K0)
+    assert np.array_equal(got, head + tail)
+
+
+def test_gemm_many_columns():
+    """N = 1.5 million columns (grid far beyond 65535 workgroups), K = 100 (masked tail only)."""
+    print("gemm many columns", flush=True)
+    M, N, K = 9, 1_500_001, 100
+    rng = np.random.default_rng(5)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    Bm = rng.standard_normal((N, K)).astype(np.float32)
+    got = host(B.bnn_xnor_gemm(B.bnn_encode(dev(A)), B.bnn_encode(dev(Bm)), K))
+    assert np.array_equal(got, oracle.gemm_pm1(A, Bm))

@@ -410,3 +410,12 @@ def test_pack_nhwc_and_fc_weight_reorder_keep_the_product():
         for o in range(n_out):
             ham = sum(bin(int(a) ^ int(b)).count("1") for a, b in zip(rows[n].tolist(), wp[o].tolist()))
             assert ref[n, o] == C * H * W - 2 * ham
+
+
+def test_gemm_refuses_k_beyond_exact_fp32_range():
+    """The float GEMM accumulates in fp32; it must say so rather than return a rounded sum."""
+    a = np.ones((1, 1 << 24), dtype=np.float32)
+    with pytest.raises(ValueError):
+        oracle.gemm_pm1(a, a)
+    k = (1 << 24) - 1
+    assert oracle.gemm_pm1(a[:, :k], a[:, :k])[0, 0] == k
