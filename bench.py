@@ -236,9 +236,15 @@ def side_measurements():
     dev = "cuda:0"
     res = {}
 
-    def t(fn, reps=50, warm=10):
+    def t(fn, reps=100, warm=100):
+        # memory-bound kernels also need tens of milliseconds of continuous work to reach their sustained rate
         s, _ = time_steps(fn, reps, warm)
         return s / reps
+
+    def kt_warm(fn, reps=20, warm=30):
+        for _ in range(warm):
+            fn()
+        return kernel_times(fn, reps)[0]
 
     # plain copy: the achievable-HBM yardstick (1 GiB read + 1 GiB written)
     n = 1 << 30
@@ -261,7 +267,7 @@ def side_measurements():
         x = torch.randn((shape.N, shape.C, shape.H, shape.W), device=dev)
         geo = (shape.kH, shape.kW, (shape.sH, shape.sW), (shape.pH, shape.pW))
         fn = lambda: B.bnn_im2col_packed(x, *geo)
-        kt, _ = kernel_times(fn, 5)
+        kt = kt_warm(fn)
         Cw = B.packed_words(shape.C)
         Kw = B.conv_kwords(shape.C, shape.kH, shape.kW)
         if "encode_nchw" in kt:
@@ -279,10 +285,12 @@ def side_measurements():
     # the same two kernels on an input several times larger than the 256 MB last-level cache:
     # encode 822 MB in / 26 MB out; gather 26 MB in / 231 MB out
     x = torch.randn((256, 256, 56, 56), device=dev)
-    kt, _ = kernel_times(lambda: B.bnn_im2col_packed(x, 3, 3, (1, 1), (1, 1)), 5)
+    kt = kt_warm(lambda: B.bnn_im2col_packed(x, 3, 3, (1, 1), (1, 1)))
     pix = 256 * 56 * 56
-    res["encode_nchw_822MB_GBs"] = round((x.numel() * 4 + pix * 4 * 8) / kt["encode_nchw"] / 1e9, 1)
+    res["encode_nchw_822MB_with_gather_between_GBs"] = round((x.numel() * 4 + pix * 4 * 8) / kt["encode_nchw"] / 1e9, 1)
     res["im2col_gather_231MB_GBs"] = round((pix * 4 * 8 + pix * 36 * 8) / kt["im2col_gather"] / 1e9, 1)
+    kt = kt_warm(lambda: B.bnn_im2col_packed(x, 1, 1, (1, 1), (0, 0)))  # pointwise: the encode alone
+    res["encode_nchw_822MB_GBs"] = round((x.numel() * 4 + pix * 4 * 8) / kt["encode_nchw"] / 1e9, 1)
     del x
     # VALU probe: measured ceiling of xor + popcount-accumulate lane-ops
     blocks, iters = 256 * 16, 2000

@@ -17,11 +17,18 @@
 //     touched after it;
 //   * B is either an explicit K-contiguous matrix or (implicit GEMM) gathered on the
 //     fly from a packed NHWC image: column = output pixel, row word = tap word, pad
-//     taps replaced by the "+1" word -- no patch matrix is ever written;
-//   * the last, partial chunk re-reads the final 8 dwords of the rows (a window that
-//     overlaps the previous chunk); the overlap and the bits past K are zeroed in both
-//     operands (A in SGPRs with scalar moves, B in the staging), so it runs the same
-//     instruction sequence as a full chunk;
+//     taps replaced by the "+1" word -- no patch matrix is ever written.  The gather has
+//     a general form (BMODE 1) and a lean one (BMODE 2) that keeps every division and all
+//     geometry out of the chunk loop: a per-slot tap-validity mask and 32-bit base offset,
+//     and a per-workgroup LDS table of tap offsets;
+//   * K tails: two leftover words run a half chunk; one or three re-read the final 8
+//     dwords of the rows (a window that overlaps the previous chunk) with the overlap and
+//     the bits past K zeroed in both operands (A in SGPRs with scalar moves, B in the
+//     staging), so they run the same instruction sequence as a full chunk; rows shorter
+//     than four words go one dword at a time;
+//   * everything a chunk needs besides the math is kept off the vector ALU and out of
+//     long-lived SGPRs (row offsets are recomputed by scalar adds per chunk), because the
+//     kernel is VALU-bound and SGPR spills are VALU instructions (v_readlane);
 //   * the store does K - 2*acc and then either writes int32 / fma(scale, acc, bias) fp32
 //     (row-major or scattered to NCHW, 256 contiguous bytes per wave store), or -- the
 //     binarizing epilogue -- takes the 2x2 max (optional), applies the fma, keeps only the
