@@ -202,13 +202,28 @@ __global__ __launch_bounds__(256) void conv2d_f32_sign27_kernel(const float *__r
     const uint32_t oh = t - n * OH;
     const int ih0 = (int)(oh * sH) - pH, iw0 = (int)(ow * sW) - pW;
     const float *xn = x + (size_t)n * 3 * H * W;
+    // Row / column validity once; every tap is loaded unconditionally from a clamped (always
+    // readable) position and zeroed afterwards: 27 independent loads, three instructions each.
+    bool rok[3], cok[3];
+    int roff[3], coff[3];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      const int ih = ih0 + j, iw = iw0 + j;
+      rok[j] = pv[q] && ih >= 0 && ih < H;
+      cok[j] = iw >= 0 && iw < W;
+      roff[j] = (ih < 0 ? 0 : (ih >= H ? H - 1 : ih)) * W;
+      coff[j] = iw < 0 ? 0 : (iw >= W ? W - 1 : iw);
+    }
+    float raw[27];
 #pragma unroll
     for (int k = 0; k < 27; ++k) {
       const int c = k / 9, r = k % 9;
-      const int ih = ih0 + r / 3, iw = iw0 + r % 3;
-      float v = 0.0f;
-      if (pv[q] && ih >= 0 && ih < H && iw >= 0 && iw < W) v = xn[((size_t)c * H + ih) * W + iw];
-      xv[q][k] = v;
+      raw[k] = xn[(size_t)c * H * W + roff[r / 3] + coff[r % 3]];
+    }
+#pragma unroll
+    for (int k = 0; k < 27; ++k) {
+      const int r = k % 9;
+      xv[q][k] = (rok[r / 3] && cok[r % 3]) ? raw[k] : 0.0f;
     }
   }
   uint32_t word[F32S_NP], hi[F32S_NP];
