@@ -59,40 +59,64 @@ __global__ __launch_bounds__(256) void control_conv_f32_mfma_kernel(ControlParam
   const float *ximg = p.x + (size_t)img * p.C * p.H * p.W;
   const int taps = p.kH * p.kW;
 
+  // load_tiles only ISSUES the loads (unconditional, from clamped positions, so none waits for
+  // another); sign, masking and the LDS writes happen in store_tiles, after the current chunk's
+  // matrix instructions have been issued.
   float ra[2][4], rb[8];
+  uint32_t va = 0, vb = 0, vin = 0;  // element is inside the matrix / the tap is inside the image
   auto load_tiles = [&](int k0) {
+    va = vb = vin = 0;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const int m = m0 + a_row + 64 * h;
+      const int mc = m < p.D ? m : p.D - 1;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int k = k0 + a_k4 + e;
-        ra[h][e] = (m < p.D && k < p.K) ? sign_pm1(p.w[(size_t)m * p.K + k]) : 0.0f;
+        const int kc = k < p.K ? k : p.K - 1;
+        va |= (uint32_t)(m < p.D && k < p.K) << (4 * h + e);
+        ra[h][e] = p.w[(size_t)mc * p.K + kc];
       }
     }
+    // (c, kh, kw) of this thread's first k by division, of the following seven by stepping
+    const uint32_t kf = (uint32_t)min(k0 + b_k8, p.K - 1);
+    int c = (int)fdiv(kf, p.divTaps);
+    const uint32_t r0 = kf - (uint32_t)c * (uint32_t)taps;
+    int kh = (int)fdiv(r0, p.divKW);
+    int kw = (int)(r0 - (uint32_t)kh * (uint32_t)p.kW);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int k = k0 + b_k8 + e;
-      float v = 0.0f;
-      if (n_ok && k < p.K) {
-        const uint32_t c = fdiv((uint32_t)k, p.divTaps);
-        const uint32_t r = (uint32_t)k - c * (uint32_t)taps;
-        const uint32_t kh = fdiv(r, p.divKW);
-        const int kw = (int)(r - kh * (uint32_t)p.kW);
-        const int ih = ih0 + (int)kh, iw = iw0 + kw;
-        v = 1.0f;  // a tap outside the image: sign(0) = +1
-        if (ih >= 0 && ih < p.H && iw >= 0 && iw < p.W) v = sign_pm1(ximg[((size_t)c * p.H + ih) * p.W + iw]);
+      const int ih = ih0 + kh, iw = iw0 + kw;
+      const bool inside = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+      const int ihc = ih < 0 ? 0 : (ih >= p.H ? p.H - 1 : ih), iwc = iw < 0 ? 0 : (iw >= p.W ? p.W - 1 : iw);
+      vb |= (uint32_t)(n_ok && k < p.K) << e;
+      vin |= (uint32_t)inside << e;
+      rb[e] = ximg[((size_t)c * p.H + ihc) * p.W + iwc];
+      // next k (stops at the last valid one, whose value is then masked by vb)
+      if (k + 1 < p.K) {
+        if (++kw == p.kW) {
+          kw = 0;
+          if (++kh == p.kH) {
+            kh = 0;
+            ++c;
+          }
+        }
       }
-      rb[e] = v;
     }
   };
   auto store_tiles = [&](int buf) {
 #pragma unroll
     for (int h = 0; h < 2; ++h)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) sA[buf][(a_k4 + e) * CT_RS + a_row + 64 * h] = ra[h][e];
+      for (int e = 0; e < 4; ++e)
+        sA[buf][(a_k4 + e) * CT_RS + a_row + 64 * h] = ((va >> (4 * h + e)) & 1u) ? sign_pm1(ra[h][e]) : 0.0f;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) sB[buf][(b_k8 + e) * CT_RS + b_pix] = rb[e];
+    for (int e = 0; e < 8; ++e) {
+      // a tap outside the image: sign(0) = +1; an element outside the matrix: 0
+      const float v = ((vin >> e) & 1u) ? sign_pm1(rb[e]) : 1.0f;
+      sB[buf][(b_k8 + e) * CT_RS + b_pix] = ((vb >> e) & 1u) ? v : 0.0f;
+    }
   };
 
   v16f acc[2][2];
