@@ -222,3 +222,13 @@ def test_prof_hook_is_inert_without_launches(L):
     assert L.bnn_prof_reset() == OK
     assert L.bnn_kernel_name(4).decode() == "xnor_gemm"
     assert L.bnn_kernel_name(1234).decode() == "unknown"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU; asking the benchmark for more must say so and fail."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr
