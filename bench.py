@@ -173,7 +173,12 @@ def build_workload(name, args):
             net.forward(x)  # fills the inter-layer buffers the per-layer closures launch on
             torch.cuda.synchronize()
             replay = net.conv_launches()
-        return dict(fn=lambda: net.forward(x), bops=2.0 * bit_macs, gemm_shapes=shapes, replay=replay,
+        split = None
+        if args.stack == "fused":
+            from paper_1911_04477_amd.stack import SplitBatch
+            sb = SplitBatch(d["layers"], d["params"], batch=batch, parts=2, device=dev)
+            split = sb
+        return dict(fn=lambda: net.forward(x), bops=2.0 * bit_macs, gemm_shapes=shapes, replay=replay, split=split, split_input=x,
                     label=f"cfg4_vgg_small_stack_b{batch}_reading{args.reading}_{args.stack}", oracle=oracle_sample,
                     extra={"batch": batch, "reading": args.reading, "activations": "packed 1-bit NHWC between layers"
                            if args.stack == "fused" else "fp32 / int32 NCHW maps between layers"})
@@ -446,6 +451,25 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu,
         "kernels_ms_per_step": {k: round(v * 1e3, 4) for k, v in kt.items()},
     }
+    if wl.get("split"):
+        # throughput mode: every batch as two half batches on two streams, successive batches free to
+        # overlap (images are independent); fork before the first step, join after the last
+        sb = wl["split"]
+        xin = wl["split_input"]
+        for _ in range(args.warmup):
+            sb.forward(xin)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        sb.fork()
+        for _ in range(args.steps):
+            sb.forward(xin, sync=False)
+        sb.join()
+        e1.record()
+        torch.cuda.synchronize()
+        s2 = e0.elapsed_time(e1) / 1e3
+        line["two_half_batches_on_two_streams"] = {"ms_per_step": round(s2 / args.steps * 1e3, 4),
+                                                   "TBOPS": round(wl["bops"] / (s2 / args.steps) / 1e12, 3)}
     if not args.no_extras:
         line["streaming"] = side_measurements()
         line["hbm_peak_GBs"] = HBM_PEAK_GBS

@@ -151,3 +151,41 @@ class VggStackFused:
                 out.append(call)
             prev = b.get("yp", None)
         return out
+
+
+class SplitBatch:
+    """The fused stack on `parts` equal slices of the batch, each on its own HIP stream (default
+    priority).  Images are independent, so the slices need no exchange; while one slice drains
+    the tail of a kernel the other's next kernel fills the idle compute units."""
+
+    def __init__(self, layers, params, batch: int, parts: int = 2, device="cuda:0"):
+        assert batch % parts == 0
+        self.parts = parts
+        self.bs = batch // parts
+        self.nets = [VggStackFused(layers, params, batch=self.bs, device=device) for _ in range(parts)]
+        self.streams = [torch.cuda.Stream(device=device) for _ in range(parts)]
+
+    def fork(self):
+        """Make the slice streams wait for what has been enqueued on the current stream."""
+        main = torch.cuda.current_stream()
+        for st in self.streams:
+            st.wait_stream(main)
+
+    def join(self):
+        """Make the current stream wait for everything enqueued on the slice streams."""
+        main = torch.cuda.current_stream()
+        for st in self.streams:
+            main.wait_stream(st)
+
+    def forward(self, x: torch.Tensor, sync: bool = True):
+        """sync=False only enqueues the slices (successive batches then overlap freely; the caller
+        forks before the first and joins after the last)."""
+        if sync:
+            self.fork()
+        outs = []
+        for i, (net, st) in enumerate(zip(self.nets, self.streams)):
+            with torch.cuda.stream(st):
+                outs.append(net.forward(x[i * self.bs:(i + 1) * self.bs]))
+        if sync:
+            self.join()
+        return outs

@@ -582,3 +582,16 @@ def test_gemm_many_columns():
     Bm = rng.standard_normal((N, K)).astype(np.float32)
     got = host(B.bnn_xnor_gemm(B.bnn_encode(dev(A)), B.bnn_encode(dev(Bm)), K))
     assert np.array_equal(got, oracle.gemm_pm1(A, Bm))
+
+
+def test_fused_stack_split_over_two_streams_matches_oracle():
+    print("split batch over two streams", flush=True)
+    from paper_1911_04477_amd.stack import SplitBatch
+    d = inputs.cfg4(batch=6)
+    sb = SplitBatch(d["layers"], d["params"], batch=6, parts=2, device=DEV)
+    x = dev(d["x"])
+    want = oracle.vgg_stack(d["x"], d["layers"], d["params"])["out"]
+    for _ in range(3):  # replays reuse the per-slice buffers
+        outs = sb.forward(x)
+        got = np.concatenate([host(o) for o in outs], axis=0)
+        assert np.array_equal(got, want)
