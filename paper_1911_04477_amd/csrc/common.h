@@ -116,4 +116,8 @@ bnn_status check_conv_geometry(int N, int C, int H, int W, int kH, int kW, int s
 bnn_status run_im2col(const float *x, int N, int C, int H, int W, int kH, int kW, int sH, int sW, int pH, int pW,
                       uint64_t *cols, void *workspace, hipStream_t s);
 
+// 3x3 convolution of a 3-channel image with fp32 NCHW output (conv.hip); validated arguments.
+bnn_status launch_conv2d_f32_k27(const float *x, const float *w, int N, int H, int W, int D, int sH, int sW, int pH,
+                                 int pW, const float *scale, const float *bias, float *out, hipStream_t s);
+
 }  // namespace bnn

@@ -180,17 +180,23 @@ __device__ __forceinline__ uint64_t f32s_uniform64(const void *ptr) {
 #define F32S_WAIT(S) \
   asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(S.a), "+s"(S.b), "+s"(S.c), "+s"(S.d), "+s"(S.sc), "+s"(S.bi))
 
+// PACK = 1: packed signs of fma(scale, acc, bias) (outp).  PACK = 0: the real-valued map itself,
+// fp32 NCHW (outf), fma(scale, acc, bias) if has_affine, else acc.
+template <int PACK>
 __global__ __launch_bounds__(256) void conv2d_f32_sign27_kernel(const float *__restrict__ x, const float *w_, int H,
                                                                 int W, int D, int sH, int sW, int pH, int pW,
                                                                 int OH, int OW, const float *scale_,
                                                                 const float *bias_, uint64_t *__restrict__ outp,
                                                                 int cw_out, FastDiv divOW, FastDiv divOH,
-                                                                uint32_t total_pix, uint32_t part) {
+                                                                uint32_t total_pix, uint32_t part,
+                                                                float *__restrict__ outf, int has_affine) {
   const uint32_t gid = blockIdx.x * 256u + threadIdx.x;
   const uint64_t wbase = f32s_uniform64(w_), sbase = f32s_uniform64(scale_), bbase = f32s_uniform64(bias_);
   // pixel q of this lane: gid + q * part (the later ones may not exist)
   float xv[F32S_NP][27];
   bool pv[F32S_NP];
+  size_t obase[F32S_NP];  // PACK = 0: element offset of (n, channel 0, oh, ow) in the NCHW output
+  const size_t ohw = (size_t)OH * OW;
 #pragma unroll
   for (int q = 0; q < F32S_NP; ++q) {
     const uint32_t p = gid + (uint32_t)q * part;
@@ -200,6 +206,7 @@ __global__ __launch_bounds__(256) void conv2d_f32_sign27_kernel(const float *__r
     const uint32_t ow = pc - t * OW;
     const uint32_t n = fdiv(t, divOH);
     const uint32_t oh = t - n * OH;
+    obase[q] = (size_t)n * D * ohw + (size_t)oh * OW + ow;
     const int ih0 = (int)(oh * sH) - pH, iw0 = (int)(ow * sW) - pW;
     const float *xn = x + (size_t)n * 3 * H * W;
     // Row / column validity once; every tap is loaded unconditionally from a clamped (always
@@ -240,6 +247,14 @@ __global__ __launch_bounds__(256) void conv2d_f32_sign27_kernel(const float *__r
       const float wk = __uint_as_float(k < 16 ? S.a[k & 15] : k < 24 ? S.b[k & 7] : k < 26 ? S.c[k & 1] : S.d);
 #pragma unroll
       for (int q = 0; q < F32S_NP; ++q) acc[q] = fmaf(xv[q][k], wk, acc[q]);
+    }
+    if constexpr (PACK == 0) {
+      if (ch < D) {
+#pragma unroll
+        for (int q = 0; q < F32S_NP; ++q)
+          if (pv[q]) outf[obase[q] + (size_t)ch * ohw] = has_affine ? fmaf(sc, acc[q], bi) : acc[q];
+      }
+      return;
     }
 #pragma unroll
     for (int q = 0; q < F32S_NP; ++q) {
@@ -379,9 +394,9 @@ extern "C" bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N,
     if (K == 27 && C == 3 && kH == 3 && kW == 3) {
       const int64_t part = (total + F32S_NP - 1) / F32S_NP;
       const dim3 grid((unsigned)((part + 255) / 256), (unsigned)bnn_packed_words(D));
-      hipLaunchKernelGGL(conv2d_f32_sign27_kernel, grid, block, 0, s, x, w, H, W, D, sH, sW, pH, pW, (int)OH, (int)OW,
-                         scale, bias, out_packed, (int)bnn_packed_words(D), FastDiv((uint32_t)OW),
-                         FastDiv((uint32_t)OH), (uint32_t)total, (uint32_t)part);
+      hipLaunchKernelGGL(conv2d_f32_sign27_kernel<1>, grid, block, 0, s, x, w, H, W, D, sH, sW, pH, pW, (int)OH,
+                         (int)OW, scale, bias, out_packed, (int)bnn_packed_words(D), FastDiv((uint32_t)OW),
+                         FastDiv((uint32_t)OH), (uint32_t)total, (uint32_t)part, (float *)nullptr, 1);
     } else {
       const dim3 grid((unsigned)((total + 255) / 256));
       hipLaunchKernelGGL(conv2d_f32_sign_kernel<0>, grid, block, 0, s, x, w, C, H, W, D, kH, kW, sH, sW, pH, pW,
@@ -391,6 +406,25 @@ extern "C" bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N,
   }
   return launch_status();
 }
+
+namespace bnn {
+// 3x3x3 real-valued convolution with fp32 NCHW output on the kernel above (arguments validated by
+// the caller; scale and bias both given or both null).
+bnn_status launch_conv2d_f32_k27(const float *x, const float *w, int N, int H, int W, int D, int sH, int sW, int pH,
+                                 int pW, const float *scale, const float *bias, float *out, hipStream_t s) {
+  const int64_t OH = bnn_conv_out_dim(H, 3, sH, pH), OW = bnn_conv_out_dim(W, 3, sW, pW);
+  const int64_t total = (int64_t)N * OH * OW;
+  const int64_t part = (total + F32S_NP - 1) / F32S_NP;
+  const dim3 grid((unsigned)((part + 255) / 256), (unsigned)bnn_packed_words(D)), block(256);
+  // without an affine map the kernel still issues its (unused) scalar loads of scale and bias:
+  // point them at readable memory
+  hipLaunchKernelGGL(conv2d_f32_sign27_kernel<0>, grid, block, 0, s, x, w, H, W, D, sH, sW, pH, pW, (int)OH, (int)OW,
+                     scale ? scale : w, bias ? bias : w, (uint64_t *)nullptr, (int)bnn_packed_words(D),
+                     FastDiv((uint32_t)OW), FastDiv((uint32_t)OH), (uint32_t)total, (uint32_t)part, out,
+                     scale ? 1 : 0);
+  return launch_status();
+}
+}  // namespace bnn
 
 extern "C" bnn_status bnn_pack_fc_weight_nhwc(const float *w, int64_t Nout, int C, int H, int W, uint64_t *w_packed,
                                               void *stream) {

@@ -359,6 +359,11 @@ extern "C" bnn_status bnn_conv2d_f32(const float *x, const float *w, int N, int 
   const int64_t total = (int64_t)N * OH * OW;
   if (total > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
+  if (C == 3 && kH == 3 && kW == 3) {
+    // the network's first layer: scalar-operand kernel shared with bnn_conv2d_f32_sign
+    ProfScope ps(KID_CONV_F32, s);
+    return launch_conv2d_f32_k27(x, w, N, H, W, D, sH, sW, pH, pW, scale, bias, out, s);
+  }
   {
     ProfScope ps(KID_CONV_F32, s);
     hipLaunchKernelGGL(conv2d_f32_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, x, w, C, H, W, D, kH,

@@ -595,3 +595,26 @@ def test_fused_stack_split_over_two_streams_matches_oracle():
         outs = sb.forward(x)
         got = np.concatenate([host(o) for o in outs], axis=0)
         assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("case", [(2, 3, 10, 9, 128, 3, 3, 1, 1, 1, 1), (3, 3, 8, 8, 70, 3, 3, 2, 2, 1, 1),
+                                  (1, 3, 7, 5, 5, 3, 3, 1, 2, 0, 1), (2, 4, 6, 6, 9, 3, 3, 1, 1, 1, 1),
+                                  (2, 3, 6, 6, 9, 5, 5, 1, 1, 2, 2)])
+@pytest.mark.parametrize("affine", [True, False])
+def test_conv2d_f32_real_valued_layer(case, affine):
+    """fp32 convolution with fp32 output: the 3-channel 3x3 form runs on the scalar-operand kernel,
+    other geometries on the general one; both follow the (c, kh, kw) fma order."""
+    print(f"conv2d_f32 case={case} affine={affine}", flush=True)
+    N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
+    shape = inputs.ConvShape(*case)
+    d = inputs.conv_inputs(shape, seed=sum(case) + 9)
+    x = inputs.inject_specials(d["x"], 8, frac=0.01, with_nan=False)
+    if affine:
+        got = host(B.bnn_conv2d_f32(dev(x), dev(d["w"]), (sH, sW), (pH, pW), dev(d["scale"]), dev(d["bias"])))
+        ref = oracle.conv2d_f32_seq(x, d["w"], (sH, sW), (pH, pW), d["scale"], d["bias"])
+    else:
+        got = host(B.bnn_conv2d_f32(dev(x), dev(d["w"]), (sH, sW), (pH, pW)))
+        ref = oracle.conv2d_f32_seq(x, d["w"], (sH, sW), (pH, pW))
+    # injected infinities of both signs meet in some sums: NaN there on both sides
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    assert np.array_equal(got, ref, equal_nan=True)
