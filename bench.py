@@ -358,6 +358,23 @@ def control_group():
     return out
 
 
+def unfused_stack(args):
+    """The same network through bnn_conv2d and the glue kernels (sign-encode, implicit GEMM with int32 /
+    fp32 NCHW maps, separate max-pool): every step of the path as its own kernel."""
+    import torch
+    from paper_1911_04477_amd import inputs
+    from paper_1911_04477_amd.stack import VggStack
+    d = inputs.cfg4(batch=256, reading=args.reading)
+    net = VggStack(d["layers"], d["params"], batch=256, device="cuda:0")
+    x = torch.from_numpy(np.ascontiguousarray(d["x"])).to("cuda:0")
+    s, _ = time_steps(lambda: net.forward(x), 300, 100)
+    kt, _ = kernel_times(lambda: net.forward(x), 10)
+    per = s / 300
+    return {"ms_per_step": round(per * 1e3, 4),
+            "TBOPS": round(2.0 * inputs.stack_bit_macs(d["layers"], 256) / per / 1e12, 2),
+            "kernels_ms": {k: round(v * 1e3, 4) for k, v in kt.items()}}
+
+
 def other_configs(args):
     out = {}
     for name in ("cfg2", "cfg3", "cfg5a", "cfg5b"):
@@ -473,6 +490,8 @@ def main():
     if not args.no_extras:
         line["streaming"] = side_measurements()
         line["hbm_peak_GBs"] = HBM_PEAK_GBS
+        if args.workload == "cfg4" and args.stack == "fused":
+            line["unfused_stack"] = unfused_stack(args)
         line["other_configs"] = other_configs(args)
         line["mfma_ablation"] = mfma_ablation()
         line["control_group"] = control_group()
