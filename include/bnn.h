@@ -143,7 +143,9 @@ bnn_status bnn_xnor_gemm_epilogue(const uint64_t *A, int64_t lda, const uint64_t
  *   out_i32   [N, D, OH, OW] int32 or NULL;  out_f32 same shape fp32 or NULL (not both NULL)
  *   scale, bias  [D] fp32, required iff out_f32 != NULL:
  *             out_f32 = fma(scale[d], (float)acc, bias[d])
- *   workspace at least bnn_conv2d_workspace_bytes(...) bytes.
+ *   workspace at least bnn_conv2d_workspace_bytes(...) bytes (device, 16-byte aligned): it
+ *             receives the packed NHWC image (1 bit per input value) the GEMM gathers its
+ *             taps from; no patch matrix is materialised.
  */
 bnn_status bnn_conv2d(const float *x, const uint64_t *w_packed, int N, int C, int H, int W, int D,
                       int kH, int kW, int sH, int sW, int pH, int pW, int32_t *out_i32,

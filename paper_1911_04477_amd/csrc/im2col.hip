@@ -132,9 +132,13 @@ extern "C" size_t bnn_im2col_workspace_bytes(int N, int C, int H, int W, int kH,
 extern "C" size_t bnn_conv2d_workspace_bytes(int N, int C, int H, int W, int kH, int kW, int sH, int sW, int pH,
                                              int pW) {
   if (!conv_geometry_ok(N, C, H, W, kH, kW, sH, sW, pH, pW)) return 0;
-  const size_t OH = (size_t)bnn_conv_out_dim(H, kH, sH, pH), OW = (size_t)bnn_conv_out_dim(W, kW, sW, pW);
-  return bnn_im2col_workspace_bytes(N, C, H, W, kH, kW, sH, sW, pH, pW) +
-         round256((size_t)N * OH * OW * (size_t)bnn_conv_kwords(C, kH, kW) * 8);
+  // the packed image the implicit GEMM gathers from: the whole input, or, for a 1x1 / pad-0
+  // convolution, only the pixels its strides sample
+  if (is_pointwise(kH, kW, pH, pW)) {
+    const size_t OH = (size_t)bnn_conv_out_dim(H, kH, sH, pH), OW = (size_t)bnn_conv_out_dim(W, kW, sW, pW);
+    return round256((size_t)N * OH * OW * (size_t)bnn_packed_words(C) * 8);
+  }
+  return round256((size_t)N * H * W * (size_t)bnn_packed_words(C) * 8);
 }
 
 extern "C" bnn_status bnn_im2col_packed(const float *x, int N, int C, int H, int W, int kH, int kW, int sH, int sW,
