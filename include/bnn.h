@@ -72,8 +72,9 @@ int64_t bnn_conv_kwords(int C, int kH, int kW);
 int64_t bnn_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad);
 
 /*
- * bnn_encode -- sign-encode a row-major fp32 matrix along its rows (section 3.1,
- * "encoded in the direction of rows"; the paper packs 32 values per uint32_t).
+ * bnn_encode -- sign-encode a row-major fp32 matrix along its rows (section 3.1: the
+ * packing runs along the rows, i.e. along the reduction axis; the paper packs 32 values
+ * per uint32_t, this library 64 per uint64_t).
  *   src     [rows, K] fp32, row stride src_ld floats (src_ld >= K)
  *   dst     [rows, ceil(K/64)] uint64, row stride dst_ld words (dst_ld >= ceil(K/64));
  *           pad bits of the last word are written as 0; words between ceil(K/64)
