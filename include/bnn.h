@@ -42,6 +42,10 @@
 #include <stddef.h>
 #include <stdint.h>
 
+/* The library is built with hidden default visibility; only what is declared here (and the
+ * test hooks of bnn_testing.h) is exported. */
+#define BNN_API __attribute__((visibility("default")))
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -60,16 +64,16 @@ typedef enum {
 typedef enum { BNN_CH_NONE = 0, BNN_CH_ROW = 1, BNN_CH_COL = 2 } bnn_ch_axis;
 
 /* Human-readable name of a status code (static storage, never NULL). */
-const char *bnn_status_str(bnn_status s);
+BNN_API const char *bnn_status_str(bnn_status s);
 
 /* ceil(K/64): uint64 words per packed row of K values; 0 for K <= 0. */
-int64_t bnn_packed_words(int64_t K);
+BNN_API int64_t bnn_packed_words(int64_t K);
 
 /* kH*kW*ceil(C/64): words per packed patch / filter row; 0 for non-positive input. */
-int64_t bnn_conv_kwords(int C, int kH, int kW);
+BNN_API int64_t bnn_conv_kwords(int C, int kH, int kW);
 
 /* floor((in + 2*pad - k)/stride) + 1, or 0 when that is not positive / arguments invalid. */
-int64_t bnn_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad);
+BNN_API int64_t bnn_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad);
 
 /*
  * bnn_encode -- sign-encode a row-major fp32 matrix along its rows (section 3.1: the
@@ -80,7 +84,7 @@ int64_t bnn_conv_out_dim(int64_t in, int64_t k, int64_t stride, int64_t pad);
  *           pad bits of the last word are written as 0; words between ceil(K/64)
  *           and dst_ld are not touched.
  */
-bnn_status bnn_encode(const float *src, int64_t rows, int64_t K, int64_t src_ld, uint64_t *dst,
+BNN_API bnn_status bnn_encode(const float *src, int64_t rows, int64_t K, int64_t src_ld, uint64_t *dst,
                       int64_t dst_ld, void *stream);
 
 /*
@@ -89,7 +93,7 @@ bnn_status bnn_encode(const float *src, int64_t rows, int64_t K, int64_t src_ld,
  *   w         [D, C, kH, kW] fp32 contiguous
  *   w_packed  [D, bnn_conv_kwords(C,kH,kW)] uint64 contiguous, (kh, kw, c) order.
  */
-bnn_status bnn_pack_conv_weight(const float *w, int D, int C, int kH, int kW, uint64_t *w_packed,
+BNN_API bnn_status bnn_pack_conv_weight(const float *w, int D, int C, int kH, int kW, uint64_t *w_packed,
                                 void *stream);
 
 /*
@@ -102,10 +106,10 @@ bnn_status bnn_pack_conv_weight(const float *w, int D, int C, int kH, int kW, ui
  *   workspace  scratch of at least bnn_im2col_workspace_bytes(...) bytes (may be NULL
  *              when that is 0); contents undefined afterwards.
  */
-bnn_status bnn_im2col_packed(const float *x, int N, int C, int H, int W, int kH, int kW, int sH,
+BNN_API bnn_status bnn_im2col_packed(const float *x, int N, int C, int H, int W, int kH, int kW, int sH,
                              int sW, int pH, int pW, uint64_t *cols, void *workspace,
                              size_t workspace_bytes, void *stream);
-size_t bnn_im2col_workspace_bytes(int N, int C, int H, int W, int kH, int kW, int sH, int sW,
+BNN_API size_t bnn_im2col_workspace_bytes(int N, int C, int H, int W, int kH, int kW, int sH, int sW,
                                   int pH, int pW);
 
 /*
@@ -117,7 +121,7 @@ size_t bnn_im2col_workspace_bytes(int N, int C, int H, int W, int kH, int kW, in
  *      (masked), whatever they hold.
  *   C  [M, N] int32 row-major, row stride ldc elements (ldc >= N).
  */
-bnn_status bnn_xnor_gemm(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb, int32_t *C,
+BNN_API bnn_status bnn_xnor_gemm(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb, int32_t *C,
                          int64_t ldc, int64_t M, int64_t N, int64_t K, void *stream);
 
 /*
@@ -129,7 +133,7 @@ bnn_status bnn_xnor_gemm(const uint64_t *A, int64_t lda, const uint64_t *B, int6
  *   scale and bias are required (M or N floats according to axis) and axis must not
  *   be BNN_CH_NONE.
  */
-bnn_status bnn_xnor_gemm_epilogue(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb,
+BNN_API bnn_status bnn_xnor_gemm_epilogue(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb,
                                   int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc, float *Y,
                                   int64_t ldy, const float *scale, const float *bias,
                                   bnn_ch_axis axis, void *stream);
@@ -148,11 +152,11 @@ bnn_status bnn_xnor_gemm_epilogue(const uint64_t *A, int64_t lda, const uint64_t
  *             receives the packed NHWC image (1 bit per input value) the GEMM gathers its
  *             taps from; no patch matrix is materialised.
  */
-bnn_status bnn_conv2d(const float *x, const uint64_t *w_packed, int N, int C, int H, int W, int D,
+BNN_API bnn_status bnn_conv2d(const float *x, const uint64_t *w_packed, int N, int C, int H, int W, int D,
                       int kH, int kW, int sH, int sW, int pH, int pW, int32_t *out_i32,
                       float *out_f32, const float *scale, const float *bias, void *workspace,
                       size_t workspace_bytes, void *stream);
-size_t bnn_conv2d_workspace_bytes(int N, int C, int H, int W, int kH, int kW, int sH, int sW, int pH,
+BNN_API size_t bnn_conv2d_workspace_bytes(int N, int C, int H, int W, int kH, int kW, int sH, int sW, int pH,
                                   int pW);
 
 /*
@@ -172,7 +176,7 @@ size_t bnn_conv2d_workspace_bytes(int N, int C, int H, int W, int kH, int kW, in
  *   scale, bias [D] are required for out_f32 and out_packed.  No workspace is needed: the
  *   patch matrix is never materialised.
  */
-bnn_status bnn_conv2d_packed(const uint64_t *x_packed, const uint64_t *w_packed, int N, int C, int H,
+BNN_API bnn_status bnn_conv2d_packed(const uint64_t *x_packed, const uint64_t *w_packed, int N, int C, int H,
                              int W, int D, int kH, int kW, int sH, int sW, int pH, int pW, int pool,
                              int32_t *out_i32, float *out_f32, uint64_t *out_packed,
                              const float *scale, const float *bias, void *stream);
@@ -183,7 +187,7 @@ bnn_status bnn_conv2d_packed(const uint64_t *x_packed, const uint64_t *w_packed,
  * the sign, written as a packed NHWC image [N, OH, OW, ceil(D/64)].  Limited to
  * C*kH*kW <= 32 taps (BNN_ERR_UNSUPPORTED otherwise).
  */
-bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N, int C, int H, int W, int D,
+BNN_API bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N, int C, int H, int W, int D,
                                int kH, int kW, int sH, int sW, int pH, int pW, const float *scale,
                                const float *bias, uint64_t *out_packed, void *stream);
 
@@ -194,7 +198,7 @@ bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N, int C, int
  * axis re-ordered to (h, w, c), each pixel padded to whole words.  (A permutation applied to
  * the reduction axis of both operands does not change the product.)
  */
-bnn_status bnn_pack_fc_weight_nhwc(const float *w, int64_t Nout, int C, int H, int W,
+BNN_API bnn_status bnn_pack_fc_weight_nhwc(const float *w, int64_t Nout, int C, int H, int W,
                                    uint64_t *w_packed, void *stream);
 
 /* ---- glue kernels of the binarized VGG-small stack (not part of the paper's kernel,
@@ -206,7 +210,7 @@ bnn_status bnn_pack_fc_weight_nhwc(const float *w, int64_t Nout, int C, int H, i
  *   in       [N, D, H, W] int32 (H, W even);  out_i32 / out_f32 [N, D, H/2, W/2], one may be NULL
  *   out_f32 = fma(scale[d], (float)max, bias[d]);  scale, bias [D] required iff out_f32.
  */
-bnn_status bnn_maxpool2x2(const int32_t *in, int N, int D, int H, int W, int32_t *out_i32,
+BNN_API bnn_status bnn_maxpool2x2(const int32_t *in, int N, int D, int H, int W, int32_t *out_i32,
                           float *out_f32, const float *scale, const float *bias, void *stream);
 
 /*
@@ -215,7 +219,7 @@ bnn_status bnn_maxpool2x2(const int32_t *in, int N, int D, int H, int W, int32_t
  * with zero padding; then, when scale != NULL, out = fma(scale[d], acc, bias[d]).
  *   x [N,C,H,W], w [D,C,kH,kW], out [N,D,OH,OW], all fp32 contiguous.
  */
-bnn_status bnn_conv2d_f32(const float *x, const float *w, int N, int C, int H, int W, int D, int kH,
+BNN_API bnn_status bnn_conv2d_f32(const float *x, const float *w, int N, int C, int H, int W, int D, int kH,
                           int kW, int sH, int sW, int pH, int pW, const float *scale,
                           const float *bias, float *out, void *stream);
 
@@ -225,7 +229,7 @@ bnn_status bnn_conv2d_f32(const float *x, const float *w, int N, int C, int H, i
  *   where xk = x[m,k], or its binary value (x >= 0 ? +1 : -1) when sign_input != 0.
  *   x [M,K], w [N,K], bias [N] or NULL, out [M,N], all fp32 contiguous.
  */
-bnn_status bnn_fc_f32(const float *x, const float *w, const float *bias, int64_t M, int64_t K,
+BNN_API bnn_status bnn_fc_f32(const float *x, const float *w, const float *bias, int64_t M, int64_t K,
                       int64_t N, int sign_input, float *out, void *stream);
 
 /* ---- ablation --------------------------------------------------------------------------- */
@@ -237,7 +241,7 @@ bnn_status bnn_fc_f32(const float *x, const float *w, const float *bias, int64_t
  * where both operands are +1; K - 2*popcount(a XOR b) follows from that count and the two
  * rows' own +1 counts.  Measured beside the VALU path, not used by any other entry point.
  */
-bnn_status bnn_xnor_gemm_mfma_i8(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb,
+BNN_API bnn_status bnn_xnor_gemm_mfma_i8(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb,
                                  int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K,
                                  void *stream);
 
@@ -253,7 +257,7 @@ bnn_status bnn_xnor_gemm_mfma_i8(const uint64_t *A, int64_t lda, const uint64_t 
  *   (device, written).  All three 16-byte aligned.  C*kH*kW < 2^24.
  * Errors as bnn_conv2d.  Not used by any other entry point.
  */
-bnn_status bnn_control_conv2d_f32(const float *x, const float *w, int N, int C, int H, int W,
+BNN_API bnn_status bnn_control_conv2d_f32(const float *x, const float *w, int N, int C, int H, int W,
                                   int D, int kH, int kW, int sH, int sW, int pH, int pW,
                                   float *out, void *stream);
 
@@ -266,12 +270,12 @@ bnn_status bnn_control_conv2d_f32(const float *x, const float *w, int N, int C, 
  * recorded between two resets; later ones run untimed.  Not thread-safe.
  */
 #define BNN_PROF_MAX_RECORDS 4096
-bnn_status bnn_prof_enable(int enable);
-bnn_status bnn_prof_reset(void);
-int64_t bnn_prof_count(void);
+BNN_API bnn_status bnn_prof_enable(int enable);
+BNN_API bnn_status bnn_prof_reset(void);
+BNN_API int64_t bnn_prof_count(void);
 /* Synchronises on record i's end event, then returns its kernel id and duration. */
-bnn_status bnn_prof_get(int64_t i, int *kernel_id, float *milliseconds);
-const char *bnn_kernel_name(int kernel_id);
+BNN_API bnn_status bnn_prof_get(int64_t i, int *kernel_id, float *milliseconds);
+BNN_API const char *bnn_kernel_name(int kernel_id);
 
 /*
  * bnn_valu_peak_probe -- a microbenchmark, not part of the method: every lane runs
@@ -279,13 +283,13 @@ const char *bnn_kernel_name(int kernel_id);
  * (2 * 64 * iters VALU lane-operations per lane) and the grid is `blocks` workgroups
  * of 256 threads.  sink [blocks*256] int32 receives a value that depends on all of them.
  */
-bnn_status bnn_valu_peak_probe(int32_t *sink, int blocks, int iters, void *stream);
+BNN_API bnn_status bnn_valu_peak_probe(int32_t *sink, int blocks, int iters, void *stream);
 
 /*
  * bnn_copy_probe -- plain device copy of n_bytes (multiple of 16) used as the yardstick
  * for achievable HBM bandwidth and for scaling hardware byte counters.
  */
-bnn_status bnn_copy_probe(const void *src, void *dst, size_t n_bytes, void *stream);
+BNN_API bnn_status bnn_copy_probe(const void *src, void *dst, size_t n_bytes, void *stream);
 
 #ifdef __cplusplus
 }

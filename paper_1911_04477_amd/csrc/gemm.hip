@@ -36,6 +36,7 @@
 // Workgroup ids are remapped so that tiles sharing a B tile run on the same XCD
 // (one L2 per XCD; hardware deals consecutive ids round-robin over the 8 XCDs).
 #include "common.h"
+#include "bnn_testing.h"
 #include "gemm_rows.inc"
 
 namespace bnn {
@@ -945,6 +946,6 @@ extern "C" bnn_status bnn_xnor_gemm_epilogue(const uint64_t *A, int64_t lda, con
   return gemm_common(A, lda, B, ldb, M, N, K, C, ldc, Y, ldy, scale, bias, axis, stream);
 }
 
-// Tuning / test hook (not declared in the public header): force a tile configuration.
+// Test and tuning switches, declared in bnn_testing.h.
 extern "C" void bnn_internal_force_gemm_cfg(int cfg) { g_force_cfg = cfg; }
 extern "C" void bnn_internal_lean_gather(int on) { g_lean_gather = on; }

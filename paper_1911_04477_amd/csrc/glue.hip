@@ -4,6 +4,7 @@
 // fixed sequential fma order so that their rounding is reproducible bit for bit (a
 // differently rounded value could flip a sign that the next binarized layer consumes).
 #include "common.h"
+#include "bnn_testing.h"
 #include "gemm_rows.inc"
 
 namespace bnn {
@@ -323,7 +324,7 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const uint4 *__restrict
 using namespace bnn;
 
 static int g_probe_mode = 0;
-// Tuning hook (not in the public header): 1 selects the scalar-operand, dependent-pair probe.
+// Measurement switch, declared in bnn_testing.h.
 extern "C" void bnn_internal_probe_mode(int mode) { g_probe_mode = mode; }
 
 extern "C" bnn_status bnn_maxpool2x2(const int32_t *in, int N, int D, int H, int W, int32_t *out_i32, float *out_f32,

@@ -17,8 +17,8 @@ def L():
     return B.lib()
 
 
-def _declared_functions():
-    src = open(os.path.join(ROOT, "include", "bnn.h")).read()
+def _declared_functions(header="bnn.h"):
+    src = open(os.path.join(ROOT, "include", header)).read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     return sorted(set(re.findall(r"\b(bnn_[a-z0-9_]+)\s*\(", src)))
 
@@ -29,6 +29,19 @@ def test_every_declared_symbol_is_exported_and_bound(L):
     for n in names:
         assert hasattr(L, n), n
     assert set(names) == set(B.SIGNATURES), set(names) ^ set(B.SIGNATURES)
+
+
+def test_nothing_undeclared_is_exported(L):
+    """The library is built with hidden visibility: its exported functions are exactly the
+    two headers' declarations (the kernels' launch handles are data symbols, not functions)."""
+    import subprocess
+    out = subprocess.check_output(["nm", "-D", "--defined-only", B.LIB_PATH], text=True)
+    funcs = {ln.split()[2] for ln in out.splitlines() if len(ln.split()) == 3 and ln.split()[1] == "T"}
+    hooks = _declared_functions("bnn_testing.h")
+    assert len(hooks) == 3
+    for n in hooks:
+        assert hasattr(L, n), n
+    assert funcs == set(_declared_functions()) | set(hooks), funcs ^ (set(_declared_functions()) | set(hooks))
 
 
 def test_status_strings(L):
