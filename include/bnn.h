@@ -35,6 +35,21 @@
  *  a packed patch / filter row has bnn_conv_kwords(C,kH,kW) = kH*kW*ceil(C/64)
  *  words.  Because the exclusive-or of two pad bits is 0 they do not contribute,
  *  and the result uses the true K = C*kH*kW.
+ *
+ * Implemented range (BNN_ERR_UNSUPPORTED beyond it; nothing is launched)
+ * ----------------------------------------------------------------------
+ *  Every limit is checked on the host.  They follow from 32-bit indices inside the kernels:
+ *   - GEMM entry points: M, N, K below 2^31; operand A at most 4 GiB (M * lda * 8 bytes).
+ *     The MFMA ablation: K below 2^29.
+ *   - Convolutions: N*H*W below 2^31 pixels; N*C*H*W at most 2^33 values; N*OH*OW at most
+ *     2^29 output pixels; N*OH*OW*bnn_conv_kwords() below 2^31 words; kH*kW at most 32767;
+ *     the packed filter bank at most 4 GiB; D*N*OH*OW at most 2^34 outputs; the packed
+ *     reduction below 2^31 bits.  Entry points that take an fp32 image additionally need
+ *     C <= 8128 and two consecutive images within 2 GiB (C*H*W*4 bytes each).
+ *   - bnn_encode: rows * ceil(K/64) below 2^37 words.
+ *   - bnn_conv2d_f32_sign: C*kH*kW at most 32.  bnn_control_conv2d_f32: C*kH*kW below 2^24.
+ *   - The glue kernels (pool, real-valued convolution, fully-connected layer): fewer than
+ *     2^31 output elements.
  */
 #ifndef BNN_H_
 #define BNN_H_

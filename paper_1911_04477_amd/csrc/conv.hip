@@ -69,8 +69,10 @@ static bnn_status conv_limits(int N, int C, int H, int W, int D, int kH, int kW,
   const int64_t OH = bnn_conv_out_dim(H, kH, sH, pH), OW = bnn_conv_out_dim(W, kW, sW, pW);
   const int64_t P = (int64_t)N * OH * OW;
   const int64_t Kw = bnn_conv_kwords(C, kH, kW);
+  // column count, 32-bit byte offsets into the filter bank, output elements, pixels, and the
+  // reduction length in bits (an int in the kernel's parameters)
   if (P > 0x7ffffff0LL / 4 || (int64_t)D * 8 * Kw > 0xffffffffLL || (int64_t)D * P > 0x7fffffffLL * 8 ||
-      (int64_t)N * H * W > 0x7fffffffLL)
+      (int64_t)N * H * W > 0x7fffffffLL || Kw * 64 > 0x7fffffffLL)
     return BNN_ERR_UNSUPPORTED;
   return BNN_OK;
 }

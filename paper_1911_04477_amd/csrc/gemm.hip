@@ -865,6 +865,9 @@ bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s) {
     if (cfg == 7 || (cfg < 0 && t32 < 512)) return launch_direct<1>(p, s, cfg == 7 ? 0 : -1);
   }
   if (bmode == 0 && emode == 0 && cfg == 9) return launch_direct<1>(p, s, 1);  // forced K split
+  // a forced value this call cannot use (the one-wave kernels read an explicit B and store
+  // int32 / fp32; anything that is not a tile configuration) selects the heuristic
+  if (cfg == 7 || cfg == 8 || cfg == 9 || cfg == 5 || cfg == 0 || cfg > 9) cfg = -1;
   if (emode == 1) {
     // tiles the packed epilogue is written for: 64 x 256 (3), 64 x 128 (6), 32 x 256 (1), 32 x 128 (4);
     // pooling needs four columns per lane (3 or 1)

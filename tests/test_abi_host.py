@@ -168,6 +168,8 @@ def test_packed_conv_errors(L):
     assert call(oi=A16) == UNSUPPORTED  # one kind of output per call
     assert call(pool=2, op=None, oi=A16) == UNSUPPORTED  # pooling only in the packed epilogue
     assert call(w=MIS) == ALIGN
+    # a reduction of 2^31 bits (8 x 8 taps of 2^25 channels) does not fit the kernel's int
+    assert call(g=(1, 1 << 25, 8, 8, 1, 8, 8, 1, 1, 0, 0)) == UNSUPPORTED
     fs = L.bnn_conv2d_f32_sign
     assert fs(A16, A16, 2, 3, 8, 8, 128, 3, 3, 1, 1, 1, 1, None, A16, A16, None) == NULL
     assert fs(A16, A16, 2, 4, 8, 8, 128, 3, 3, 1, 1, 1, 1, A16, A16, A16, None) == UNSUPPORTED  # 36 taps > 32

@@ -374,11 +374,12 @@ PACKED_CASES = CONV_CASES + [
 ]
 
 
-@pytest.mark.parametrize("cfg", [1, 3, 4, 6])
+@pytest.mark.parametrize("cfg", [1, 3, 4, 6, 9])
 @pytest.mark.parametrize("case", PACKED_CASES[-11:] + PACKED_CASES[1:4])
 def test_conv2d_packed_forced_tiles(case, cfg):
     """The binarizing epilogue on every tile shape it is written for (the pooled form only
-    exists for the four-column tiles; other requests fall back to a legal tile)."""
+    exists for the four-column tiles; other requests fall back to a legal tile, and 9, a
+    configuration only the explicit GEMM has, to the heuristic)."""
     print(f"conv2d_packed forced cfg={cfg} case={case}", flush=True)
     N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
     shape = inputs.ConvShape(*case)
