@@ -34,8 +34,12 @@ VALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12  # 39.32
 BOPS_PER_LANEOP = 32.0  # 2 lane-instructions (xor, popcount-accumulate) per 32 bit-MACs = 64 binary ops
 
 # HBM bytes per launch of xnor_gemm_kernel from rocprofv3 counters, valid for the default workload only
-# (profiles/xnor_gemm_cfg4_fused_stack_b256.md: FETCH_SIZE 1869.8 KiB x 2.00 + WRITE_SIZE 972.8 KiB, five launches per step).
-GEMM_TRAFFIC_BYTES = 4.83e6
+# (profiles/xnor_gemm_cfg4_fused_stack_b256.md, average of the five launches of a step).  Reads: the
+# L2's read requests by size class, 128 B x a + 64 B x b = 2751 KiB (exact: the same counters read
+# 1 GiB for a 1 GiB copy); writes: WRITE_SIZE 972.8 KiB.  The FETCH_SIZE metric scaled by the copy
+# kernel's factor (x 2.00) over-prices this kernel's 64-byte requests and would give 4.83e6.
+GEMM_TRAFFIC_BYTES = 3.81e6
+GEMM_TRAFFIC_BYTES_FETCH_SIZE_SCALED = 4.83e6
 
 
 def parse_args():
@@ -445,12 +449,14 @@ def main():
         "bound": "alu", "achieved": round(achieved, 3), "peak": round(VALU_PEAK_TLANEOPS, 2),
         "unit": "Tlaneop/s", "frac": round(achieved / VALU_PEAK_TLANEOPS, 4),
         "traffic": GEMM_TRAFFIC_BYTES if default_wl else None,
+        "traffic_fetch_size_x2": GEMM_TRAFFIC_BYTES_FETCH_SIZE_SCALED if default_wl else None,
         "launches_per_step": dom_n, "avg_launch_ms": round(dom_s / dom_n * 1e3, 4),
         "per_launch": per_launch,
         "gemm_only_TBOPS": round(wl["bops"] / gemm_s / 1e12, 2),
         "timing": method,
         "note": "achieved = 2*M*N*ceil(K/32) lane-ops of the dominant kernel's launches in one step / their summed "
-                "duration; traffic = HBM bytes per launch of that kernel (rocprofv3 FETCH_SIZE*2.00 + WRITE_SIZE)",
+                "duration; traffic = HBM bytes per launch of that kernel (rocprofv3: read requests by size class + WRITE_SIZE; "
+                "traffic_fetch_size_x2 = FETCH_SIZE scaled by the copy kernel's factor + WRITE_SIZE, an over-estimate here)",
     }
 
     cpu = None
