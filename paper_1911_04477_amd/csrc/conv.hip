@@ -138,163 +138,232 @@ __global__ __launch_bounds__(256) void conv2d_f32_sign_kernel(const float *__res
   }
 }
 
-// 3x3x3 specialization (K = 27).  A workgroup computes 64 output channels (one stored word) of
-// its pixels; each lane owns F32S_NP output pixels (p + q * part), so one
-// set of scalar weight loads feeds 27 * F32S_NP fused multiply-adds, and the loads of the next channel
-// (27 weights, scale, bias: 29 SGPRs) are issued before the current channel is computed: the
-// scalar-memory latency is covered by compute instead of being waited for per channel.
-// Channels run from high to low inside each group of 32, so the sign bit is shifted in with a
-// single add-with-carry (word = 2*word + bit).  Loads, wait and carry trick are inline asm;
-// the last load statement of a set names the first tap of the first pixel as in/out operand, which
-// keeps the multiply-adds of the channel being computed behind the loads of the next one.
-// Every SGPR an in-flight load will write is an operand of the wait that follows, so it stays
-// reserved until the data has arrived.
-constexpr int F32S_NP = 2;
-using f32s_u32x2 = uint32_t __attribute__((ext_vector_type(2)));
-using f32s_u32x8 = uint32_t __attribute__((ext_vector_type(8)));
-using f32s_u32x16 = uint32_t __attribute__((ext_vector_type(16)));
-struct F32sWSet {
-  f32s_u32x16 a;  // taps 0..15
-  f32s_u32x8 b;   // taps 16..23
-  f32s_u32x2 c;   // taps 24, 25
-  uint32_t d;     // tap 26
-  uint32_t sc, bi;
-};
+// ---- the 3x3x3 layer (K = 27) on the fp32 matrix cores --------------------------------------
+// V_MFMA_F32_32X32X1_2B_F32 multiplies a 32 x 1 column by a 1 x 32 row and adds the 32 x 32
+// product to its accumulator, for two independent blocks at once; one reduction step at a time,
+// each output element goes through exactly the fused multiply-add chain over (c, kh, kw) that
+// the general kernel above runs (checked bit for bit against fmaf chains, denormals, infinities
+// and signed zeros included), at twice the rate of unpacked vector multiply-adds.
+//   rows (operand A)    : 32 output channels; lanes l and l + 32 hold the same filter tap
+//   columns (operand B) : the wave's 64 pixels, block 0 = pixels 0..31, block 1 = pixels 32..63;
+//                         lane l supplies the patch value of pixel l
+//   accumulators        : register r of block b, lane l = channel 8*(r/4) + 4*(l/32) + r%4 of
+//                         pixel 32*b + l%32
+// A workgroup stages the filter taps of up to 128 channels in LDS ([tap][channel], odd row
+// stride), then each wave walks over its pixel groups: 27 clamped loads per lane, four channel
+// groups x 27 matrix instructions, and the affine map + sign on the vector unit (which runs
+// beside the matrix unit of the other resident waves).
+constexpr int C1M_CH = 128;   // channels per workgroup (blockIdx.y)
+constexpr int C1M_RS = 129;   // LDS row stride of the tap-major filter tile
+typedef float c1m_v32f __attribute__((ext_vector_type(32)));
 
-__device__ __forceinline__ uint64_t f32s_uniform64(const void *ptr) {
-  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)ptr);
-  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uintptr_t)ptr >> 32));
-  return ((uint64_t)hi << 32) | (uint64_t)lo;
+__device__ __forceinline__ uint32_t c1m_spread_nibbles(uint32_t m) {
+  // nibble q of a 16-bit mask -> bits 8q .. 8q+3
+  return (m & 0xFu) | ((m & 0xF0u) << 4) | ((m & 0xF00u) << 8) | ((m & 0xF000u) << 12);
 }
 
-#define F32S_LOAD(S, ch)                                                                                   \
-  do {                                                                                                     \
-    const uint32_t ch_ = (uint32_t)__builtin_amdgcn_readfirstlane((int)(ch));                              \
-    const uint32_t o0_ = ch_ * 108u, o1_ = o0_ + 0x40u, o2_ = o0_ + 0x60u, o3_ = o0_ + 0x68u;              \
-    const uint32_t o4_ = ch_ * 4u;                                                                         \
-    asm volatile("s_load_dwordx16 %0, %1, %2" : "=s"(S.a) : "s"(wbase), "s"(o0_));                         \
-    asm volatile("s_load_dwordx8 %0, %1, %2" : "=s"(S.b) : "s"(wbase), "s"(o1_));                          \
-    asm volatile("s_load_dwordx2 %0, %1, %2" : "=s"(S.c) : "s"(wbase), "s"(o2_));                          \
-    asm volatile("s_load_dword %0, %1, %2" : "=s"(S.d) : "s"(wbase), "s"(o3_));                            \
-    asm volatile("s_load_dword %0, %1, %2" : "=s"(S.sc) : "s"(sbase), "s"(o4_));                           \
-    asm volatile("s_load_dword %0, %2, %3" : "=s"(S.bi), "+v"(xv[0][0]) : "s"(bbase), "s"(o4_));           \
-  } while (0)
-#define F32S_WAIT(S) \
-  asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(S.a), "+s"(S.b), "+s"(S.c), "+s"(S.d), "+s"(S.sc), "+s"(S.bi))
+// Stage the filter taps of channels ch0 .. ch0 + 127 tap-major in LDS (read [channel][tap]
+// contiguously; channels past D are zero) and their scale / bias (past D, or without an affine
+// map: fma(0, acc, -1) < 0, so such bits are 0).
+__device__ __forceinline__ void c1m_stage_filters(float *sTap, float *sSc, float *sBi, const float *__restrict__ w,
+                                                  const float *__restrict__ scale, const float *__restrict__ bias,
+                                                  int ch0, int nch, bool affine) {
+  const int tid = threadIdx.x;
+  for (int idx = tid; idx < 27 * C1M_CH; idx += 256) {
+    const int ch = idx / 27, k = idx - 27 * ch;
+    sTap[k * C1M_RS + ch] = ch < nch ? w[(size_t)ch0 * 27 + idx] : 0.0f;
+  }
+  if (tid < C1M_CH) {
+    const bool real = tid < nch && affine;
+    sSc[tid] = real ? scale[ch0 + tid] : 0.0f;
+    sBi[tid] = real ? bias[ch0 + tid] : -1.0f;
+  }
+}
 
-// PACK = 1: packed signs of fma(scale, acc, bias) (outp).  PACK = 0: the real-valued map itself,
-// fp32 NCHW (outf), fma(scale, acc, bias) if has_affine, else acc.
-template <int PACK>
-__global__ __launch_bounds__(256) void conv2d_f32_sign27_kernel(const float *__restrict__ x, const float *w_, int H,
-                                                                int W, int D, int sH, int sW, int pH, int pW,
-                                                                int OH, int OW, const float *scale_,
-                                                                const float *bias_, uint64_t *__restrict__ outp,
-                                                                int cw_out, FastDiv divOW, FastDiv divOH,
-                                                                uint32_t total_pix, uint32_t part,
-                                                                float *__restrict__ outf, int has_affine) {
-  const uint32_t gid = blockIdx.x * 256u + threadIdx.x;
-  const uint64_t wbase = f32s_uniform64(w_), sbase = f32s_uniform64(scale_), bbase = f32s_uniform64(bias_);
-  // pixel q of this lane: gid + q * part (the later ones may not exist)
-  float xv[F32S_NP][27];
-  bool pv[F32S_NP];
-  size_t obase[F32S_NP];  // PACK = 0: element offset of (n, channel 0, oh, ow) in the NCHW output
+// Issue the 27 loads of pixel p's patch: every tap unconditionally from a clamped (always
+// readable) position; bit r of `inside` says whether tap (r / 3, r % 3) lies in the image.
+__device__ __forceinline__ void c1m_issue_patch(const float *__restrict__ x, uint32_t p, uint32_t total_pix, int H,
+                                                int W, int sH, int sW, int pH, int pW, int OH, int OW, FastDiv divOW,
+                                                FastDiv divOH, float (&raw)[27], uint32_t &inside) {
+  const bool pv = p < total_pix;
+  const uint32_t pc = pv ? p : 0u;
+  const uint32_t t = fdiv(pc, divOW);
+  const uint32_t ow = pc - t * OW;
+  const uint32_t n = fdiv(t, divOH);
+  const uint32_t oh = t - n * OH;
+  const int ih0 = (int)(oh * sH) - pH, iw0 = (int)(ow * sW) - pW;
+  const float *xn = x + (size_t)n * 3 * H * W;
+  uint32_t rok = 0, cok = 0;
+  int roff[3], coff[3];
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    const int ih = ih0 + j, iw = iw0 + j;
+    rok |= (uint32_t)(pv && ih >= 0 && ih < H) << j;
+    cok |= (uint32_t)(iw >= 0 && iw < W) << j;
+    roff[j] = (ih < 0 ? 0 : (ih >= H ? H - 1 : ih)) * W;
+    coff[j] = iw < 0 ? 0 : (iw >= W ? W - 1 : iw);
+  }
+  inside = 0;
+#pragma unroll
+  for (int r = 0; r < 9; ++r) inside |= (((rok >> (r / 3)) & (cok >> (r % 3))) & 1u) << r;
+#pragma unroll
+  for (int k = 0; k < 27; ++k) {
+    const int c = k / 9, r = k % 9;
+    raw[k] = xn[(size_t)c * H * W + roff[r / 3] + coff[r % 3]];
+  }
+}
+
+// 27 dependent matrix instructions: channel group g (32 channels) x this wave's 64 pixels.
+__device__ __forceinline__ c1m_v32f c1m_chain(const float *wg, const float (&xv)[27]) {
+  c1m_v32f acc;
+#pragma unroll
+  for (int r = 0; r < 32; ++r) acc[r] = 0.0f;
+#pragma unroll
+  for (int k = 0; k < 27; ++k) acc = __builtin_amdgcn_mfma_f32_32x32x1f32(wg[k * C1M_RS], xv[k], acc, 0, 0, 0);
+  return acc;
+}
+
+// Affine map and sign of one channel group's accumulators -> the 32 channel bits of this
+// lane's own pixel.  Lanes l and l + 32 hold the two channel halves of a pixel: l < 32 keeps
+// its block-0 bits and receives the partner's, l >= 32 likewise with block 1.
+__device__ __forceinline__ uint32_t c1m_sign_bits(const c1m_v32f &acc, const float *sSc, const float *sBi, int g,
+                                                  int half) {
+  // rows descend so that every sign is shifted in with one add-with-carry: m = 2 * m + (y >= 0)
+  uint32_t m0 = 0u, m1 = 0u;
+#pragma unroll
+  for (int q = 3; q >= 0; --q) {
+    const float4 sc = *reinterpret_cast<const float4 *>(sSc + 32 * g + 8 * q + 4 * half);
+    const float4 bi = *reinterpret_cast<const float4 *>(sBi + 32 * g + 8 * q + 4 * half);
+    const float scv[4] = {sc.x, sc.y, sc.z, sc.w}, biv[4] = {bi.x, bi.y, bi.z, bi.w};
+#pragma unroll
+    for (int e = 3; e >= 0; --e) {
+      const int rr = 4 * q + e;
+      const float y0 = fmaf(scv[e], acc[rr], biv[e]), y1 = fmaf(scv[e], acc[16 + rr], biv[e]);
+      asm("v_cmp_le_f32 vcc, 0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(m0) : "v"(y0) : "vcc");
+      asm("v_cmp_le_f32 vcc, 0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(m1) : "v"(y1) : "vcc");
+    }
+  }
+  const uint32_t own = half ? m1 : m0;
+  const uint32_t got = (uint32_t)__shfl_xor((int)(half ? m0 : m1), 32);
+  const uint32_t lo = half ? got : own, hi = half ? own : got;  // channels 8q+0..3 / 8q+4..7
+  return c1m_spread_nibbles(lo) | (c1m_spread_nibbles(hi) << 4);
+}
+
+// Packed-sign output.
+// On this chip the fp32 matrix instructions and the vector ALU do not run side by side (vector
+// instructions placed between the matrix instructions of a chain lengthen it by their full
+// issue time, measured), so nothing is gained by interleaving the sign step with the next chain:
+// the loop is the plain sequence loads, one chain per group of 32 channels followed by its sign
+// step, store, and several resident waves per SIMD cover the load latency.
+__global__ __launch_bounds__(256) void conv2d_f32_k27_mfma_sign_kernel(
+    const float *__restrict__ x, const float *__restrict__ w, int H, int W, int D, int sH, int sW, int pH, int pW,
+    int OH, int OW, const float *__restrict__ scale, const float *__restrict__ bias, uint64_t *__restrict__ outp,
+    int cw_out, FastDiv divOW, FastDiv divOH, uint32_t total_pix, uint32_t ngroups, int groups_per_wave) {
+  __shared__ float sTap[27 * C1M_RS];
+  __shared__ __attribute__((aligned(16))) float sSc[C1M_CH];
+  __shared__ __attribute__((aligned(16))) float sBi[C1M_CH];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int half = lane >> 5, l32 = lane & 31;
+  const int ch0 = C1M_CH * (int)blockIdx.y;
+  const uint32_t g_first = ((uint32_t)blockIdx.x * 4u + (uint32_t)wave) * (uint32_t)groups_per_wave;
+  const uint32_t g_end = min(g_first + (uint32_t)groups_per_wave, ngroups);
+  const int word0 = 2 * (int)blockIdx.y;
+  // the first patch is requested before the filters are staged, so the two latencies overlap
+  // (a wave without pixel groups loads pixel 0's and discards it)
+  float xv[27];
+  uint32_t inside;
+  c1m_issue_patch(x, g_first * 64u + (uint32_t)lane, total_pix, H, W, sH, sW, pH, pW, OH, OW, divOW, divOH, xv, inside);
+  const int nch = min(C1M_CH, D - ch0);  // >= 1 by the grid
+  c1m_stage_filters(sTap, sSc, sBi, w, scale, bias, ch0, nch, true);
+  __syncthreads();  // the only barrier: from here on the waves run independently
+
+  for (uint32_t grp = g_first; grp < g_end; ++grp) {  // wave-uniform bounds
+    const uint32_t p = grp * 64u + (uint32_t)lane;
+    if (grp != g_first)
+      c1m_issue_patch(x, p, total_pix, H, W, sH, sW, pH, pW, OH, OW, divOW, divOH, xv, inside);
+#pragma unroll
+    for (int k = 0; k < 27; ++k) xv[k] = ((inside >> (k % 9)) & 1u) ? xv[k] : 0.0f;
+    uint32_t gw[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int g = 0; g < C1M_CH / 32; ++g) {
+      if (32 * g >= nch) break;  // workgroup-uniform: groups past the last channel keep zero bits
+      const c1m_v32f acc = c1m_chain(sTap + 32 * g + l32, xv);
+      gw[g] = c1m_sign_bits(acc, sSc, sBi, g, half);
+    }
+    if (p < total_pix) {
+      uint64_t *o = outp + (size_t)p * cw_out + word0;
+      o[0] = ((uint64_t)gw[1] << 32) | gw[0];
+      if (word0 + 1 < cw_out) o[1] = ((uint64_t)gw[3] << 32) | gw[2];
+    }
+  }
+}
+
+// fp32 NCHW output (the map itself, with the affine map if has_affine), same chains, no pipelining.
+__global__ __launch_bounds__(256) void conv2d_f32_k27_mfma_kernel(const float *__restrict__ x,
+                                                                  const float *__restrict__ w, int H, int W, int D,
+                                                                  int sH, int sW, int pH, int pW, int OH, int OW,
+                                                                  const float *__restrict__ scale,
+                                                                  const float *__restrict__ bias, FastDiv divOW,
+                                                                  FastDiv divOH, uint32_t total_pix, uint32_t ngroups,
+                                                                  int groups_per_wave, float *__restrict__ outf,
+                                                                  int has_affine) {
+  __shared__ float sTap[27 * C1M_RS];
+  __shared__ float sSc[C1M_CH], sBi[C1M_CH];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int half = lane >> 5, l32 = lane & 31;
+  const int ch0 = C1M_CH * (int)blockIdx.y;
+  const int nch = min(C1M_CH, D - ch0);  // >= 1 by the grid
+  c1m_stage_filters(sTap, sSc, sBi, w, scale, bias, ch0, nch, has_affine != 0);
+  __syncthreads();  // the only barrier
+
   const size_t ohw = (size_t)OH * OW;
+  const uint32_t g_first = ((uint32_t)blockIdx.x * 4u + (uint32_t)wave) * (uint32_t)groups_per_wave;
+  for (int gi = 0; gi < groups_per_wave; ++gi) {
+    const uint32_t grp = g_first + (uint32_t)gi;
+    if (grp >= ngroups) break;  // wave-uniform
+    float xv[27];
+    uint32_t inside;
+    c1m_issue_patch(x, grp * 64u + (uint32_t)lane, total_pix, H, W, sH, sW, pH, pW, OH, OW, divOW, divOH, xv, inside);
 #pragma unroll
-  for (int q = 0; q < F32S_NP; ++q) {
-    const uint32_t p = gid + (uint32_t)q * part;
-    pv[q] = gid < part && p < total_pix;
-    const uint32_t pc = pv[q] ? p : 0u;
-    const uint32_t t = fdiv(pc, divOW);
-    const uint32_t ow = pc - t * OW;
-    const uint32_t n = fdiv(t, divOH);
-    const uint32_t oh = t - n * OH;
-    obase[q] = (size_t)n * D * ohw + (size_t)oh * OW + ow;
-    const int ih0 = (int)(oh * sH) - pH, iw0 = (int)(ow * sW) - pW;
-    const float *xn = x + (size_t)n * 3 * H * W;
-    // Row / column validity once; every tap is loaded unconditionally from a clamped (always
-    // readable) position and zeroed afterwards: 27 independent loads, three instructions each.
-    bool rok[3], cok[3];
-    int roff[3], coff[3];
+    for (int k = 0; k < 27; ++k) xv[k] = ((inside >> (k % 9)) & 1u) ? xv[k] : 0.0f;
+    // NCHW offsets of (image, channel 0, pixel) for the two pixels this lane holds results of
+    size_t obase[2];
+    bool ov[2];
 #pragma unroll
-    for (int j = 0; j < 3; ++j) {
-      const int ih = ih0 + j, iw = iw0 + j;
-      rok[j] = pv[q] && ih >= 0 && ih < H;
-      cok[j] = iw >= 0 && iw < W;
-      roff[j] = (ih < 0 ? 0 : (ih >= H ? H - 1 : ih)) * W;
-      coff[j] = iw < 0 ? 0 : (iw >= W ? W - 1 : iw);
+    for (int b = 0; b < 2; ++b) {
+      const uint32_t q = grp * 64u + 32u * (uint32_t)b + (uint32_t)l32;
+      ov[b] = q < total_pix;
+      const uint32_t qc = ov[b] ? q : 0u;
+      const uint32_t qn = fdiv(fdiv(qc, divOW), divOH);
+      obase[b] = (size_t)qn * D * ohw + ((size_t)qc - (size_t)qn * ohw);
     }
-    float raw[27];
+#pragma unroll 1
+    for (int g = 0; g < C1M_CH / 32; ++g) {
+      if (32 * g >= nch) break;  // workgroup-uniform
+      const c1m_v32f acc = c1m_chain(sTap + 32 * g + l32, xv);
 #pragma unroll
-    for (int k = 0; k < 27; ++k) {
-      const int c = k / 9, r = k % 9;
-      raw[k] = xn[(size_t)c * H * W + roff[r / 3] + coff[r % 3]];
-    }
+      for (int b = 0; b < 2; ++b)
 #pragma unroll
-    for (int k = 0; k < 27; ++k) {
-      const int r = k % 9;
-      xv[q][k] = (rok[r / 3] && cok[r % 3]) ? raw[k] : 0.0f;
-    }
-  }
-  uint32_t word[F32S_NP], hi[F32S_NP];
-#pragma unroll
-  for (int q = 0; q < F32S_NP; ++q) word[q] = hi[q] = 0u;
-  auto compute = [&](const F32sWSet &S, int ch) {
-    const float sc = __uint_as_float(S.sc), bi = __uint_as_float(S.bi);
-    // the pixels' chains advance together: every multiply-add has independent neighbours
-    float acc[F32S_NP];
-#pragma unroll
-    for (int q = 0; q < F32S_NP; ++q) acc[q] = 0.0f;
-#pragma unroll
-    for (int k = 0; k < 27; ++k) {
-      const float wk = __uint_as_float(k < 16 ? S.a[k & 15] : k < 24 ? S.b[k & 7] : k < 26 ? S.c[k & 1] : S.d);
-#pragma unroll
-      for (int q = 0; q < F32S_NP; ++q) acc[q] = fmaf(xv[q][k], wk, acc[q]);
-    }
-    if constexpr (PACK == 0) {
-      if (ch < D) {
-#pragma unroll
-        for (int q = 0; q < F32S_NP; ++q)
-          if (pv[q]) outf[obase[q] + (size_t)ch * ohw] = has_affine ? fmaf(sc, acc[q], bi) : acc[q];
-      }
-      return;
-    }
-#pragma unroll
-    for (int q = 0; q < F32S_NP; ++q) {
-      const float y = fmaf(sc, acc[q], bi);
-      // word = 2 * word + (y >= 0)
-      asm("v_cmp_le_f32 vcc, 0, %1\n\tv_addc_co_u32 %0, vcc, %0, %0, vcc" : "+v"(word[q]) : "v"(y) : "vcc");
-    }
-    if ((ch & 31) == 0) {
-      // a group of 32 channels is complete: drop the bits of channels past D, emit
-      const int g = ch >> 5;
-      const int left = D - ch;  // real channels in this group
-      const uint32_t vm = left >= 32 ? 0xffffffffu : ((1u << left) - 1u);
-#pragma unroll
-      for (int q = 0; q < F32S_NP; ++q) {
-        const uint32_t wv = left > 0 ? (word[q] & vm) : 0u;
-        if (g & 1) {
-          hi[q] = wv;  // channels descend: the upper half of a word is finished first
-        } else {
-          const uint32_t p = gid + (uint32_t)q * part;
-          if (pv[q]) outp[(size_t)p * cw_out + (g >> 1)] = ((uint64_t)hi[q] << 32) | wv;
+        for (int rr = 0; rr < 16; ++rr) {
+          const int chl = 32 * g + 8 * (rr >> 2) + 4 * half + (rr & 3);
+          if (chl < nch && ov[b]) {
+            const float a = acc[16 * b + rr];
+            outf[obase[b] + (size_t)(ch0 + chl) * ohw] = has_affine ? fmaf(sSc[chl], a, sBi[chl]) : a;
+          }
         }
-        word[q] = 0u;
-      }
     }
-  };
-  // blockIdx.y selects the 64 output channels (one stored word per pixel) this workgroup computes
-  const int ch_lo = 64 * (int)blockIdx.y, ch_hi = ch_lo + 63;
-  const int last = D - 1;
-  F32sWSet SA, SB;
-  F32S_LOAD(SA, (ch_hi < last ? ch_hi : last));
-  for (int ch = ch_hi; ch > ch_lo; ch -= 2) {
-    F32S_WAIT(SA);
-    F32S_LOAD(SB, (ch - 1 < last ? ch - 1 : last));
-    compute(SA, ch);
-    F32S_WAIT(SB);
-    if (ch - 2 >= ch_lo) F32S_LOAD(SA, (ch - 2 < last ? ch - 2 : last));
-    compute(SB, ch - 1);
   }
+}
+
+// Launch shape of the matrix-core first layer: one wave per `*gpw` groups of 64 pixels (enough
+// groups per wave to amortise the filter staging, enough waves to give every SIMD two).
+static dim3 c1m_grid(int64_t total_pix, int D, int *gpw, int64_t wave_slots = 2048) {
+  const int64_t ngroups = (total_pix + 63) / 64;
+  int64_t g = ngroups / wave_slots;
+  g = g < 1 ? 1 : (g > 8 ? 8 : g);
+  *gpw = (int)g;
+  const int64_t waves = (ngroups + g - 1) / g;
+  return dim3((unsigned)((waves + 3) / 4), (unsigned)((D + C1M_CH - 1) / C1M_CH));
 }
 
 // Filter bank of a fully-connected layer whose input is a flattened NCHW map [C, H, W],
@@ -394,11 +463,13 @@ extern "C" bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N,
     ProfScope ps(KID_CONV_F32_SIGN, s);
     const dim3 block(256);
     if (K == 27 && C == 3 && kH == 3 && kW == 3) {
-      const int64_t part = (total + F32S_NP - 1) / F32S_NP;
-      const dim3 grid((unsigned)((part + 255) / 256), (unsigned)bnn_packed_words(D));
-      hipLaunchKernelGGL(conv2d_f32_sign27_kernel<1>, grid, block, 0, s, x, w, H, W, D, sH, sW, pH, pW, (int)OH,
-                         (int)OW, scale, bias, out_packed, (int)bnn_packed_words(D), FastDiv((uint32_t)OW),
-                         FastDiv((uint32_t)OH), (uint32_t)total, (uint32_t)part, (float *)nullptr, 1);
+      int gpw;
+      const dim3 grid = c1m_grid(total, D, &gpw);
+      const uint32_t ngroups = (uint32_t)((total + 63) / 64);
+      const int cw = (int)bnn_packed_words(D);
+      const FastDiv dOW((uint32_t)OW), dOH((uint32_t)OH);
+      hipLaunchKernelGGL(conv2d_f32_k27_mfma_sign_kernel, grid, block, 0, s, x, w, H, W, D, sH, sW, pH, pW, (int)OH,
+                         (int)OW, scale, bias, out_packed, cw, dOW, dOH, (uint32_t)total, ngroups, gpw);
     } else {
       const dim3 grid((unsigned)((total + 255) / 256));
       hipLaunchKernelGGL(conv2d_f32_sign_kernel<0>, grid, block, 0, s, x, w, C, H, W, D, kH, kW, sH, sW, pH, pW,
@@ -416,14 +487,11 @@ bnn_status launch_conv2d_f32_k27(const float *x, const float *w, int N, int H, i
                                  int pW, const float *scale, const float *bias, float *out, hipStream_t s) {
   const int64_t OH = bnn_conv_out_dim(H, 3, sH, pH), OW = bnn_conv_out_dim(W, 3, sW, pW);
   const int64_t total = (int64_t)N * OH * OW;
-  const int64_t part = (total + F32S_NP - 1) / F32S_NP;
-  const dim3 grid((unsigned)((part + 255) / 256), (unsigned)bnn_packed_words(D)), block(256);
-  // without an affine map the kernel still issues its (unused) scalar loads of scale and bias:
-  // point them at readable memory
-  hipLaunchKernelGGL(conv2d_f32_sign27_kernel<0>, grid, block, 0, s, x, w, H, W, D, sH, sW, pH, pW, (int)OH, (int)OW,
-                     scale ? scale : w, bias ? bias : w, (uint64_t *)nullptr, (int)bnn_packed_words(D),
-                     FastDiv((uint32_t)OW), FastDiv((uint32_t)OH), (uint32_t)total, (uint32_t)part, out,
-                     scale ? 1 : 0);
+  int gpw;
+  const dim3 grid = c1m_grid(total, D, &gpw), block(256);
+  hipLaunchKernelGGL(conv2d_f32_k27_mfma_kernel, grid, block, 0, s, x, w, H, W, D, sH, sW, pH, pW, (int)OH, (int)OW,
+                     scale, bias, FastDiv((uint32_t)OW), FastDiv((uint32_t)OH), (uint32_t)total,
+                     (uint32_t)((total + 63) / 64), gpw, out, scale ? 1 : 0);
   return launch_status();
 }
 }  // namespace bnn

@@ -361,7 +361,7 @@ extern "C" bnn_status bnn_conv2d_f32(const float *x, const float *w, int N, int 
   if (total > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
   if (C == 3 && kH == 3 && kW == 3) {
-    // the network's first layer: scalar-operand kernel shared with bnn_conv2d_f32_sign
+    // the network's first layer: the matrix-core chains shared with bnn_conv2d_f32_sign
     ProfScope ps(KID_CONV_F32, s);
     return launch_conv2d_f32_k27(x, w, N, H, W, D, sH, sW, pH, pW, scale, bias, out, s);
   }

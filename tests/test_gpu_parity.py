@@ -347,7 +347,11 @@ def _u64dev(a):
 
 
 @pytest.mark.parametrize("case", [(2, 3, 10, 9, 128, 3, 3, 1, 1, 1, 1), (3, 3, 8, 8, 70, 3, 3, 2, 2, 1, 1),
-                                  (1, 1, 6, 6, 5, 5, 5, 1, 1, 2, 2), (2, 2, 7, 7, 200, 3, 3, 1, 1, 0, 0)])
+                                  (1, 1, 6, 6, 5, 5, 5, 1, 1, 2, 2), (2, 2, 7, 7, 200, 3, 3, 1, 1, 0, 0),
+                                  (2, 3, 10, 9, 200, 3, 3, 1, 1, 1, 1),    # two channel chunks, the second partial
+                                  (1, 3, 40, 37, 257, 3, 3, 1, 1, 1, 1),   # five words per pixel, 24 pixel groups
+                                  (3, 3, 9, 11, 31, 3, 3, 1, 2, 0, 1),     # fewer than 32 channels
+                                  (2, 3, 5, 5, 1, 3, 3, 1, 1, 1, 1)])      # one channel
 def test_conv2d_f32_sign_matches_oracle(case):
     print(f"conv2d_f32_sign case={case}", flush=True)
     N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
@@ -598,12 +602,33 @@ def test_fused_stack_split_over_two_streams_matches_oracle():
         assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("xs,ws", [(1e-25, 1e-15), (1e-38, 1.0), (1e18, 1e18), (1.0, 1e-44)])
+def test_conv2d_f32_first_layer_chain_rounds_like_fmaf(xs, ws):
+    """The 3x3x3 layer runs its (c, kh, kw) chain on the fp32 matrix cores, one reduction step
+    per instruction; it must round exactly like the oracle's fmaf chain also where products or
+    sums are subnormal, underflow to zero, or overflow."""
+    case = (2, 3, 9, 8, 45, 3, 3, 1, 1, 1, 1)
+    print(f"conv2d_f32 extreme magnitudes xs={xs} ws={ws}", flush=True)
+    shape = inputs.ConvShape(*case)
+    d = inputs.conv_inputs(shape, seed=77)
+    x = (d["x"].astype(np.float64) * xs).astype(np.float32)
+    w = (d["w"].astype(np.float64) * ws).astype(np.float32)
+    got = host(B.bnn_conv2d_f32(dev(x), dev(w), (1, 1), (1, 1)))
+    ref = oracle.conv2d_f32_seq(x, w, (1, 1), (1, 1))
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    assert np.array_equal(got.view(np.uint32)[~np.isnan(ref)], ref.view(np.uint32)[~np.isnan(ref)])
+    sc = np.ones(45, np.float32)
+    bi = np.zeros(45, np.float32)
+    gp = as_u64(B.bnn_conv2d_f32_sign(dev(x), dev(w), dev(sc), dev(bi), (1, 1), (1, 1)))
+    assert np.array_equal(gp, oracle.pack_nhwc(oracle.conv2d_f32_seq(x, w, (1, 1), (1, 1), sc, bi)))
+
+
 @pytest.mark.parametrize("case", [(2, 3, 10, 9, 128, 3, 3, 1, 1, 1, 1), (3, 3, 8, 8, 70, 3, 3, 2, 2, 1, 1),
                                   (1, 3, 7, 5, 5, 3, 3, 1, 2, 0, 1), (2, 4, 6, 6, 9, 3, 3, 1, 1, 1, 1),
-                                  (2, 3, 6, 6, 9, 5, 5, 1, 1, 2, 2)])
+                                  (2, 3, 6, 6, 9, 5, 5, 1, 1, 2, 2), (1, 3, 20, 19, 161, 3, 3, 1, 1, 1, 1)])
 @pytest.mark.parametrize("affine", [True, False])
 def test_conv2d_f32_real_valued_layer(case, affine):
-    """fp32 convolution with fp32 output: the 3-channel 3x3 form runs on the scalar-operand kernel,
+    """fp32 convolution with fp32 output: the 3-channel 3x3 form runs on the matrix-core kernel,
     other geometries on the general one; both follow the (c, kh, kw) fma order."""
     print(f"conv2d_f32 case={case} affine={affine}", flush=True)
     N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
