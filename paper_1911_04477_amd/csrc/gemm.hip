@@ -120,6 +120,18 @@ __device__ __forceinline__ void store_tile(const int (&acc)[TM][TN], int m0, int
   const uint32_t OHW = kp->OHW;
   FastDiv divOHW;
   divOHW.d = kp->divOHW.d; divOHW.mul = kp->divOHW.mul; divOHW.shift = kp->divOHW.shift;
+  // per-row affine constants once per tile (wave-uniform: scalar loads; rows past M re-read row M - 1)
+  float scr[TM], bir[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    scr[i] = 1.0f;
+    bir[i] = 0.0f;
+    if (Yp && axis == BNN_CH_ROW) {
+      const int mi = min(m0 + i, M - 1);
+      scr[i] = scale[mi];
+      bir[i] = bias[mi];
+    }
+  }
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int n = nbase + j * 64;
@@ -139,13 +151,10 @@ __device__ __forceinline__ void store_tile(const int (&acc)[TM][TN], int m0, int
     for (int i = 0; i < TM; ++i) {
       if (m0 + i < M) {
         const int v = Kformula - 2 * acc[i][j];
-        if (cp) *cp = v;
+        if (cp) __builtin_nontemporal_store(v, cp);
         if (yp) {
-          if (axis == BNN_CH_ROW) {
-            sc = scale[m0 + i];
-            bi = bias[m0 + i];
-          }
-          *yp = fmaf(sc, (float)v, bi);
+          const float s1 = axis == BNN_CH_ROW ? scr[i] : sc, b1 = axis == BNN_CH_ROW ? bir[i] : bi;
+          __builtin_nontemporal_store(fmaf(s1, (float)v, b1), yp);
         }
       }
       if (cp) cp += ldc;
