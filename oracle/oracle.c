@@ -14,8 +14,10 @@
  * section 3.2, torch's CPU conv2d / matmul on +-1 tensors, exact rational
  * arithmetic for the epilogue.
  * The fp32 glue (oracle_conv2d_f32_seq, oracle_fc_f32_seq) fixes a summation
- * order the paper does not give; its rounding is a convention: parity unpinned
- * beyond a float64 sanity bound.
+ * order the paper does not give; that convention is pinned by hand-worked cases
+ * in which another order, a separately rounded product or skipped padding taps
+ * give a different number, and the indexing by small-integer inputs (exact in
+ * any order) against torch's float64 convolution / matmul.
  *
  * Build: gcc -O3 -march=x86-64-v3 -ffp-contract=off -fopenmp -shared -fPIC
  */

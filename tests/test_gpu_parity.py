@@ -602,6 +602,29 @@ def test_fused_stack_split_over_two_streams_matches_oracle():
         assert np.array_equal(got, want)
 
 
+def test_f32_glue_hand_worked_cases(golden_dir):
+    """The hand-worked order / rounding cases of the real-valued layers, straight against the
+    stored values (no oracle in between)."""
+    import json
+    import os
+    with open(os.path.join(golden_dir, "f32_glue_order_examples.json")) as f:
+        cases = json.load(f)
+    f32 = lambda v: np.array([float(t) for t in v], dtype=np.float32)
+    for c in cases["conv"]:
+        print(f"conv2d_f32 hand-worked {c['name']}", flush=True)
+        x, w = f32(c["x"]).reshape(c["x_shape"]), f32(c["w"]).reshape(c["w_shape"])
+        args = (dev(x), dev(w), tuple(c["stride"]), tuple(c["pad"]))
+        if "scale" in c:
+            args += (dev(f32(c["scale"])), dev(f32(c["bias"])))
+        got = host(B.bnn_conv2d_f32(*args)).ravel()
+        assert np.array_equal(got, f32(c["out"]), equal_nan=True), (c["name"], got)
+    for c in cases["fc"]:
+        print(f"fc_f32 hand-worked {c['name']}", flush=True)
+        x, w = np.array(c["x"], dtype=np.float32), np.array(c["w"], dtype=np.float32)
+        got = host(B.bnn_fc_f32(dev(x), dev(w), dev(f32(c["bias"])), sign_input=c["sign_input"]))
+        assert np.array_equal(got, np.array(c["out"], dtype=np.float32)), (c["name"], got)
+
+
 @pytest.mark.parametrize("xs,ws", [(1e-25, 1e-15), (1e-38, 1.0), (1e18, 1e18), (1.0, 1e-44)])
 def test_conv2d_f32_first_layer_chain_rounds_like_fmaf(xs, ws):
     """The 3x3x3 layer runs its (c, kh, kw) chain on the fp32 matrix cores, one reduction step
@@ -621,6 +644,16 @@ def test_conv2d_f32_first_layer_chain_rounds_like_fmaf(xs, ws):
     bi = np.zeros(45, np.float32)
     gp = as_u64(B.bnn_conv2d_f32_sign(dev(x), dev(w), dev(sc), dev(bi), (1, 1), (1, 1)))
     assert np.array_equal(gp, oracle.pack_nhwc(oracle.conv2d_f32_seq(x, w, (1, 1), (1, 1), sc, bi)))
+    # an infinite filter tap: NaN wherever it meets a padding zero, on both sides
+    w2 = w.copy()
+    w2[0, 0, 0, 0] = np.inf
+    w2[7, 2, 2, 1] = -np.inf
+    got = host(B.bnn_conv2d_f32(dev(x), dev(w2), (1, 1), (1, 1)))
+    ref = oracle.conv2d_f32_seq(x, w2, (1, 1), (1, 1))
+    assert np.isnan(ref).any() and np.array_equal(np.isnan(got), np.isnan(ref))
+    assert np.array_equal(got, ref, equal_nan=True)
+    gp = as_u64(B.bnn_conv2d_f32_sign(dev(x), dev(w2), dev(sc), dev(bi), (1, 1), (1, 1)))
+    assert np.array_equal(gp, oracle.pack_nhwc(oracle.conv2d_f32_seq(x, w2, (1, 1), (1, 1), sc, bi)))
 
 
 @pytest.mark.parametrize("case", [(2, 3, 10, 9, 128, 3, 3, 1, 1, 1, 1), (3, 3, 8, 8, 70, 3, 3, 2, 2, 1, 1),
