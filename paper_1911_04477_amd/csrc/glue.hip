@@ -80,99 +80,128 @@ __global__ __launch_bounds__(256) void conv2d_f32_kernel(const float *__restrict
   }
 }
 
-// One workgroup per (16 rows of x, 16 outputs).  The whole K extent (up to FC_KC) of those
-// rows of x and w is staged in LDS with every global load in flight at once, so memory latency
-// is paid once; then thread (output j, row r) runs the sequential fma chain over k, which is
-// the floor for this layer (the summation order over k is ascending as specified, so a chain
-// cannot be split).  Longer rows take several passes over the two LDS tiles.
-constexpr int FC_ROWS = 16;
+// One workgroup per (ROWS rows of x, 16 outputs).  The whole K extent (up to FC_KC) of those
+// rows of x and w is staged in LDS by all 256 threads with every global load in flight at once,
+// so memory latency is paid once; then thread (output j, row r) runs the sequential fma chain
+// over k, which is the floor for this layer (the summation order over k is ascending as
+// specified, so a chain cannot be split).  Longer rows take several passes over the two LDS
+// tiles.  The chains read both operands from LDS (32 bytes per 4 steps and thread), so LDS
+// bandwidth, not the chain, bounds a workgroup: ROWS = 4 (one computing wave, the other three
+// only stage) spreads a small layer over four times as many compute units as ROWS = 16.
 constexpr int FC_NB = 16;
 constexpr int FC_KC = 1024;
 constexpr int FC_RS = FC_KC + 4;  // row stride in floats: 16-byte reads of different rows spread over the banks
+template <int ROWS>
 __global__ __launch_bounds__(256) void fc_f32_kernel(const float *__restrict__ x, const float *__restrict__ w,
                                                      const float *__restrict__ bias, int64_t M, int64_t K, int64_t N,
                                                      int sign_input, float *__restrict__ out, int n_groups) {
-  __shared__ __attribute__((aligned(16))) float sx[FC_ROWS * FC_RS];
+  __shared__ __attribute__((aligned(16))) float sx[ROWS * FC_RS];
   __shared__ __attribute__((aligned(16))) float sw[FC_NB * FC_RS];
-  const int64_t m0 = (int64_t)(blockIdx.x / n_groups) * FC_ROWS;
+  const int64_t m0 = (int64_t)(blockIdx.x / n_groups) * ROWS;
   const int64_t n0 = (int64_t)(blockIdx.x % n_groups) * FC_NB;
   const int tid = threadIdx.x;
-  const int r = tid & 15, j = tid >> 4;
+  const int r = tid % ROWS, j = tid / ROWS;
+  const bool computes = tid < ROWS * FC_NB;  // whole waves: ROWS * 16 is a multiple of 64
   const bool vec = (K & 3) == 0;  // rows start 16-byte aligned (the bases are)
   float acc = 0.0f;
   for (int64_t k0 = 0; k0 < K; k0 += FC_KC) {
     const int kc = (int)((K - k0) < FC_KC ? (K - k0) : FC_KC);
     if (vec) {
-      constexpr int Q = FC_KC / 4;             // 16-byte pieces per row
-      constexpr int PER = FC_ROWS * Q / 256;   // pieces per thread and operand
-      float4 vx[PER], vw[PER];
+      constexpr int Q = FC_KC / 4;                    // 16-byte pieces per row
+      constexpr int PER = (ROWS + FC_NB) * Q / 256;   // pieces per thread: rows of x first, then rows of w
+      float4 v[PER];
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
         const int idx = i * 256 + tid;
         const int rr = idx / Q, kk = (idx % Q) * 4;
-        vx[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-        vw[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (kk < kc) {
-          if (m0 + rr < M) vx[i] = *reinterpret_cast<const float4 *>(x + (m0 + rr) * K + k0 + kk);
-          if (n0 + rr < N) vw[i] = *reinterpret_cast<const float4 *>(w + (n0 + rr) * K + k0 + kk);
+          if (rr < ROWS) {
+            if (m0 + rr < M) v[i] = *reinterpret_cast<const float4 *>(x + (m0 + rr) * K + k0 + kk);
+          } else if (n0 + (rr - ROWS) < N) {
+            v[i] = *reinterpret_cast<const float4 *>(w + (n0 + (rr - ROWS)) * K + k0 + kk);
+          }
         }
       }
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
         const int idx = i * 256 + tid;
         const int rr = idx / Q, kk = (idx % Q) * 4;
-        float4 v = vx[i];
-        if (sign_input) {
-          v.x = v.x >= 0.0f ? 1.0f : -1.0f; v.y = v.y >= 0.0f ? 1.0f : -1.0f;
-          v.z = v.z >= 0.0f ? 1.0f : -1.0f; v.w = v.w >= 0.0f ? 1.0f : -1.0f;
+        float4 t = v[i];
+        if (rr < ROWS) {
+          if (sign_input) {
+            t.x = t.x >= 0.0f ? 1.0f : -1.0f; t.y = t.y >= 0.0f ? 1.0f : -1.0f;
+            t.z = t.z >= 0.0f ? 1.0f : -1.0f; t.w = t.w >= 0.0f ? 1.0f : -1.0f;
+          }
+          *reinterpret_cast<float4 *>(&sx[rr * FC_RS + kk]) = t;
+        } else {
+          *reinterpret_cast<float4 *>(&sw[(rr - ROWS) * FC_RS + kk]) = t;
         }
-        *reinterpret_cast<float4 *>(&sx[rr * FC_RS + kk]) = v;
-        *reinterpret_cast<float4 *>(&sw[rr * FC_RS + kk]) = vw[i];
       }
     } else {
-      for (int idx = tid; idx < FC_ROWS * FC_KC; idx += 256) {
+      for (int idx = tid; idx < (ROWS + FC_NB) * FC_KC; idx += 256) {
         const int rr = idx / FC_KC, kk = idx % FC_KC;
-        float xv = 0.0f, wv = 0.0f;
+        float t = 0.0f;
         if (kk < kc) {
-          if (m0 + rr < M) xv = x[(m0 + rr) * K + k0 + kk];
-          if (n0 + rr < N) wv = w[(n0 + rr) * K + k0 + kk];
-          if (sign_input) xv = xv >= 0.0f ? 1.0f : -1.0f;
+          if (rr < ROWS) {
+            if (m0 + rr < M) t = x[(m0 + rr) * K + k0 + kk];
+            if (sign_input) t = t >= 0.0f ? 1.0f : -1.0f;
+          } else if (n0 + (rr - ROWS) < N) {
+            t = w[(n0 + (rr - ROWS)) * K + k0 + kk];
+          }
         }
-        sx[rr * FC_RS + kk] = xv;
-        sw[rr * FC_RS + kk] = wv;
+        if (rr < ROWS) sx[rr * FC_RS + kk] = t;
+        else sw[(rr - ROWS) * FC_RS + kk] = t;
       }
     }
     __syncthreads();
-    const float *px = &sx[r * FC_RS], *pw = &sw[j * FC_RS];
-    int kk = 0;
-    // 32 k per round: all sixteen 16-byte LDS reads are issued before the chain consumes them
-    for (; kk + 32 <= kc; kk += 32) {
-      float4 a[8], b[8];
+    if (computes) {
+      const float *px = &sx[r * FC_RS], *pw = &sw[j * FC_RS];
+      int kk = 0;
+      // 32 k per round; the sixteen 16-byte LDS reads of the next round are issued before the
+      // chain of the current one, so their latency hides behind its 32 dependent fma
+      if (kc >= 32) {
+        float4 a[8], b[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        a[u] = *reinterpret_cast<const float4 *>(px + kk + 4 * u);
-        b[u] = *reinterpret_cast<const float4 *>(pw + kk + 4 * u);
-      }
+        for (int u = 0; u < 8; ++u) {
+          a[u] = *reinterpret_cast<const float4 *>(px + 4 * u);
+          b[u] = *reinterpret_cast<const float4 *>(pw + 4 * u);
+        }
+        for (; kk + 32 <= kc; kk += 32) {
+          float4 an[8], bn[8];
+          const int nx = kk + 64 <= kc ? kk + 32 : kk;  // last round: re-read this one (unused)
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        acc = fmaf(a[u].x, b[u].x, acc);
-        acc = fmaf(a[u].y, b[u].y, acc);
-        acc = fmaf(a[u].z, b[u].z, acc);
-        acc = fmaf(a[u].w, b[u].w, acc);
+          for (int u = 0; u < 8; ++u) {
+            an[u] = *reinterpret_cast<const float4 *>(px + nx + 4 * u);
+            bn[u] = *reinterpret_cast<const float4 *>(pw + nx + 4 * u);
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            acc = fmaf(a[u].x, b[u].x, acc);
+            acc = fmaf(a[u].y, b[u].y, acc);
+            acc = fmaf(a[u].z, b[u].z, acc);
+            acc = fmaf(a[u].w, b[u].w, acc);
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            a[u] = an[u];
+            b[u] = bn[u];
+          }
+        }
       }
+      for (; kk + 4 <= kc; kk += 4) {
+        const float4 a = *reinterpret_cast<const float4 *>(px + kk);
+        const float4 b = *reinterpret_cast<const float4 *>(pw + kk);
+        acc = fmaf(a.x, b.x, acc);
+        acc = fmaf(a.y, b.y, acc);
+        acc = fmaf(a.z, b.z, acc);
+        acc = fmaf(a.w, b.w, acc);
+      }
+      for (; kk < kc; ++kk) acc = fmaf(px[kk], pw[kk], acc);
     }
-    for (; kk + 4 <= kc; kk += 4) {
-      const float4 a = *reinterpret_cast<const float4 *>(px + kk);
-      const float4 b = *reinterpret_cast<const float4 *>(pw + kk);
-      acc = fmaf(a.x, b.x, acc);
-      acc = fmaf(a.y, b.y, acc);
-      acc = fmaf(a.z, b.z, acc);
-      acc = fmaf(a.w, b.w, acc);
-    }
-    for (; kk < kc; ++kk) acc = fmaf(px[kk], pw[kk], acc);
     __syncthreads();
   }
-  if (m0 + r < M && n0 + j < N) {
+  if (computes && m0 + r < M && n0 + j < N) {
     if (bias) acc = acc + bias[n0 + j];
     out[(m0 + r) * N + n0 + j] = acc;
   }
@@ -381,13 +410,18 @@ extern "C" bnn_status bnn_fc_f32(const float *x, const float *w, const float *bi
   if (!x || !w || !out) return BNN_ERR_NULL;
   if (!aligned16(x) || !aligned16(w) || !aligned16(out)) return BNN_ERR_ALIGN;
   const int64_t n_groups = (N + FC_NB - 1) / FC_NB;
-  const int64_t m_groups = (M + FC_ROWS - 1) / FC_ROWS;
+  // 16 rows per workgroup when that already gives every compute unit one; else 4
+  const bool small = ((M + 15) / 16) * n_groups < 256;
+  const int64_t m_groups = small ? (M + 3) / 4 : (M + 15) / 16;
   if (m_groups * n_groups > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   hipStream_t s = (hipStream_t)stream;
   {
     ProfScope ps(KID_FC_F32, s);
-    hipLaunchKernelGGL(fc_f32_kernel, dim3((unsigned)(m_groups * n_groups)), dim3(256), 0, s, x, w, bias, M, K, N, sign_input,
-                       out, (int)n_groups);
+    const dim3 grid((unsigned)(m_groups * n_groups)), block(256);
+    if (small)
+      hipLaunchKernelGGL(fc_f32_kernel<4>, grid, block, 0, s, x, w, bias, M, K, N, sign_input, out, (int)n_groups);
+    else
+      hipLaunchKernelGGL(fc_f32_kernel<16>, grid, block, 0, s, x, w, bias, M, K, N, sign_input, out, (int)n_groups);
   }
   return launch_status();
 }

@@ -296,6 +296,24 @@ def test_maxpool_and_f32_glue():
         assert np.array_equal(got, oracle.fc_f32_seq(xf, wf, bf, sign_input=sgn))
 
 
+@pytest.mark.parametrize("M,K,N", [(256, 1024, 10), (6, 100, 10), (5, 1023, 3), (33, 2500, 37), (1, 4, 1),
+                                   (4100, 64, 20), (300, 1030, 250)])
+@pytest.mark.parametrize("sgn", [False, True])
+def test_fc_f32_matches_oracle(M, K, N, sgn):
+    """Both workgroup shapes (4 and 16 rows), rows of several LDS passes, K off the 16-byte grid,
+    output counts off the group of 16; with and without bias."""
+    print(f"fc_f32 M={M} K={K} N={N} sign={sgn}", flush=True)
+    rng = np.random.default_rng(M * 7 + K + N)
+    xf = inputs.inject_specials(rng.standard_normal((M, K)).astype(np.float32), 4, frac=0.002, with_nan=False)
+    wf = rng.standard_normal((N, K)).astype(np.float32)
+    bf = rng.standard_normal(N).astype(np.float32)
+    got = host(B.bnn_fc_f32(dev(xf), dev(wf), dev(bf), sign_input=sgn))
+    ref = oracle.fc_f32_seq(xf, wf, bf, sign_input=sgn)
+    assert np.array_equal(got, ref, equal_nan=True)
+    got = host(B.bnn_fc_f32(dev(xf), dev(wf), None, sign_input=sgn))
+    assert np.array_equal(got, oracle.fc_f32_seq(xf, wf, None, sign_input=sgn), equal_nan=True)
+
+
 @pytest.mark.parametrize("reading", ["A", "B"])
 def test_cfg4_stack_small_batch_every_layer(reading):
     print(f"cfg4 stack batch 4 reading {reading}", flush=True)
