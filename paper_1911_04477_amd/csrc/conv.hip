@@ -255,7 +255,7 @@ __device__ __forceinline__ uint32_t c1m_sign_bits(const c1m_v32f &acc, const flo
 // issue time, measured), so nothing is gained by interleaving the sign step with the next chain:
 // the loop is the plain sequence loads, one chain per group of 32 channels followed by its sign
 // step, store, and several resident waves per SIMD cover the load latency.
-__global__ __launch_bounds__(256) void conv2d_f32_k27_mfma_sign_kernel(
+__global__ __launch_bounds__(256, 4) void conv2d_f32_k27_mfma_sign_kernel(
     const float *__restrict__ x, const float *__restrict__ w, int H, int W, int D, int sH, int sW, int pH, int pW,
     int OH, int OW, const float *__restrict__ scale, const float *__restrict__ bias, uint64_t *__restrict__ outp,
     int cw_out, FastDiv divOW, FastDiv divOH, uint32_t total_pix, uint32_t ngroups, int groups_per_wave) {
@@ -464,7 +464,7 @@ extern "C" bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N,
     const dim3 block(256);
     if (K == 27 && C == 3 && kH == 3 && kW == 3) {
       int gpw;
-      const dim3 grid = c1m_grid(total, D, &gpw);
+      const dim3 grid = c1m_grid(total, D, &gpw, 4096);  // four resident waves per SIMD
       const uint32_t ngroups = (uint32_t)((total + 63) / 64);
       const int cw = (int)bnn_packed_words(D);
       const FastDiv dOW((uint32_t)OW), dOH((uint32_t)OH);
