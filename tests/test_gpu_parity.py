@@ -168,6 +168,34 @@ def test_gemm_leading_dimensions():
     assert np.all(out[:, N:] == -7)
 
 
+@pytest.mark.parametrize("axis", ["row", "col"])
+@pytest.mark.parametrize("cfg", [-1, 1, 2, 3, 4, 6, 7, 8, 9])
+@pytest.mark.parametrize("M,N,K", [(37, 150, 300), (130, 515, 1100), (8, 64, 64)])
+def test_gemm_fp32_epilogue_both_axes(M, N, K, cfg, axis):
+    """y = fma(scale[ch], float(acc), bias[ch]) with the channel along rows or columns, with and
+    without the int32 result beside it, on every tile configuration."""
+    print(f"gemm epilogue M={M} N={N} K={K} cfg={cfg} axis={axis}", flush=True)
+    rng = np.random.default_rng(M + N + K + cfg)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    Bm = rng.standard_normal((N, K)).astype(np.float32)
+    nch = M if axis == "row" else N
+    sc = ((rng.random(nch) + 0.5) * rng.choice([-1.0, 1.0], nch)).astype(np.float32)
+    bi = rng.standard_normal(nch).astype(np.float32)
+    Ap, Bp = B.bnn_encode(dev(A)), B.bnn_encode(dev(Bm))
+    ref = oracle.gemm_pm1(A, Bm)
+    yref = oracle.scale_bias(ref, sc, bi, axis)
+    ax = B.CH_ROW if axis == "row" else B.CH_COL
+    B.lib().bnn_internal_force_gemm_cfg(cfg)
+    try:
+        C, Y = B.bnn_xnor_gemm_epilogue(Ap, Bp, K, dev(sc), dev(bi), ax, want_int=True)
+        assert np.array_equal(host(C), ref)
+        assert np.array_equal(host(Y), yref)
+        C, Y = B.bnn_xnor_gemm_epilogue(Ap, Bp, K, dev(sc), dev(bi), ax, want_int=False)
+        assert C is None and np.array_equal(host(Y), yref)
+    finally:
+        B.lib().bnn_internal_force_gemm_cfg(-1)
+
+
 def test_gemm_deterministic_twice():
     print("gemm determinism", flush=True)
     d = inputs.cfg1()
@@ -455,6 +483,39 @@ def _conv2d_packed_all_output_kinds(case):
         pref = oracle.scale_bias(oracle.maxpool2x2_i32(ref), d["scale"], d["bias"], "nchw")
         got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, pool=2, scale=sc, bias=bi, out="packed"))
         assert np.array_equal(got, oracle.pack_nhwc(pref))
+
+
+def _random_geometries(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        N = int(rng.integers(1, 4))
+        C = int(rng.choice([1, 3, 17, 63, 64, 65, 100, 128, 129, 192, 200, 256]))
+        H, W = int(rng.integers(3, 13)), int(rng.integers(3, 13))
+        kH, kW = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        sH, sW = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        pH, pW = int(rng.integers(0, 3)), int(rng.integers(0, 3))
+        D = int(rng.choice([1, 7, 31, 32, 33, 64, 65, 100, 130]))
+        if H + 2 * pH < kH or W + 2 * pW < kW:
+            continue
+        out.append((N, C, H, W, D, kH, kW, sH, sW, pH, pW))
+    return out
+
+
+@pytest.mark.parametrize("case", _random_geometries(36, seed=20191104))
+def test_conv_entry_points_on_random_geometries(case):
+    """Seeded random shapes (kernel sizes 1..5, strides 1..3, pads 0..2, channel counts on and
+    off the word grid) through bnn_conv2d, bnn_im2col_packed and every output kind of
+    bnn_conv2d_packed."""
+    print(f"random geometry case={case}", flush=True)
+    N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
+    shape = inputs.ConvShape(*case)
+    d = inputs.conv_inputs(shape, seed=sum(case) + 11)
+    _conv_parity(shape, d, full=True)
+    _conv2d_packed_all_output_kinds(case)
+    x = inputs.inject_specials(d["x"], 5, frac=0.01)
+    cols = as_u64(B.bnn_im2col_packed(dev(x), kH, kW, (sH, sW), (pH, pW)))
+    assert np.array_equal(cols, oracle.im2col_packed(x, kH, kW, (sH, sW), (pH, pW)))
 
 
 def test_conv2d_packed_negative_scale_and_pool_order():
