@@ -309,6 +309,34 @@ def side_measurements():
     return res
 
 
+def small_batch_latency(args):
+    """One pass of the fused stack at small batch sizes, launched eagerly (eight launches through
+    the Python binding) and as one replay of a captured HIP graph: a pass at these sizes is
+    shorter than its launches take to submit."""
+    import torch
+    from paper_1911_04477_amd import inputs
+    from paper_1911_04477_amd.stack import VggStackFused
+    out = {}
+    for batch in (1, 8, 32):
+        d = inputs.cfg4(batch=batch, reading=args.reading)
+        net = VggStackFused(d["layers"], d["params"], batch=batch, device="cuda:0")
+        x = torch.from_numpy(d["x"]).to("cuda:0")
+        net.capture(x)
+        res = {}
+        for name, fn in (("eager", lambda: net.forward(x)), ("graph", net.replay)):
+            for _ in range(200):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(500):
+                fn()
+            torch.cuda.synchronize()
+            res[name + "_us"] = round((time.perf_counter() - t0) / 500 * 1e6, 1)
+        res["images_per_s_graph"] = round(batch / (res["graph_us"] * 1e-6))
+        out[f"batch{batch}"] = res
+    return out
+
+
 def mfma_ablation():
     """The int8-MFMA-on-0/1 ablation beside the VALU GEMM on the GEMM view of cfg 5a and cfg 3."""
     import torch
@@ -498,6 +526,7 @@ def main():
         line["hbm_peak_GBs"] = HBM_PEAK_GBS
         if args.workload == "cfg4" and args.stack == "fused":
             line["unfused_stack"] = unfused_stack(args)
+            line["small_batch_latency"] = small_batch_latency(args)
         line["other_configs"] = other_configs(args)
         line["mfma_ablation"] = mfma_ablation()
         line["control_group"] = control_group()

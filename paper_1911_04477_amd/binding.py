@@ -192,11 +192,15 @@ def bnn_control_conv2d_f32(x: torch.Tensor, w: torch.Tensor, stride=(1, 1), pad=
 
 
 def bnn_xnor_gemm_epilogue(A: torch.Tensor, B: torch.Tensor, K: int, scale: torch.Tensor, bias: torch.Tensor,
-                           axis: int, want_int: bool = False) -> Tuple[Optional[torch.Tensor], torch.Tensor]:
+                           axis: int, want_int: bool = False,
+                           out_y: Optional[torch.Tensor] = None) -> Tuple[Optional[torch.Tensor], torch.Tensor]:
     _dev(A, torch.int64, "A")
     _dev(B, torch.int64, "B")
     M, N = A.shape[0], B.shape[0]
-    Y = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    if out_y is not None:
+        _dev(out_y, torch.float32, "out_y")
+        assert out_y.shape == (M, N) and out_y.is_contiguous()
+    Y = out_y if out_y is not None else torch.empty((M, N), dtype=torch.float32, device=A.device)
     C = torch.empty((M, N), dtype=torch.int32, device=A.device) if want_int else None
     lda = A.stride(0) if M > 1 else max(A.shape[1], 1)
     ldb = B.stride(0) if N > 1 else max(B.shape[1], 1)

@@ -107,11 +107,37 @@ class VggStackFused:
                 d["wp"] = B.bnn_pack_fc_weight_nhwc(d["w"], C, H, W)
                 d["kbits"] = H * W * B.packed_words(C) * 64
                 d["ktrue"] = L.cin
+                b["y"] = torch.empty((batch, L.cout), dtype=torch.float32, device=self.dev)
             elif L.kind == "fc_f32":
                 b["y"] = torch.empty((batch, L.cout), dtype=torch.float32, device=self.dev)
             self.p.append(d)
             self.buf.append(b)
+        self._graph = None
         torch.cuda.synchronize(self.dev)
+
+    def capture(self, x: torch.Tensor) -> None:
+        """Record one forward pass reading x (its storage, not its present contents) into a HIP
+        graph.  Every buffer of the pass is preallocated and the library neither allocates nor
+        synchronises, so the graph holds exactly the pass's kernel launches; replay() re-issues
+        them with one submission, which is what matters at batch sizes where a pass is shorter
+        than its eight launches take to submit."""
+        side = torch.cuda.Stream(device=self.dev)  # default priority
+        side.wait_stream(torch.cuda.current_stream(self.dev))
+        with torch.cuda.stream(side):
+            self.forward(x)  # every code path has run once before capture
+        torch.cuda.current_stream(self.dev).wait_stream(side)
+        torch.cuda.synchronize(self.dev)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            self._graph_out = self.forward(x)
+        self._graph = g
+
+    def replay(self) -> torch.Tensor:
+        """Re-run the captured pass on the current contents of the captured input."""
+        if self._graph is None:
+            raise RuntimeError("capture() first")
+        self._graph.replay()
+        return self._graph_out
 
     def forward(self, x: torch.Tensor, keep: bool = False):
         h = x
@@ -127,7 +153,8 @@ class VggStackFused:
                 # formula takes the true K through the epilogue entry point's K argument
                 rows = h.view(self.batch, -1)
                 assert rows.shape[1] * 64 == p["kbits"] == p["ktrue"], "channel counts here are multiples of 64"
-                _, h = B.bnn_xnor_gemm_epilogue(rows, p["wp"], p["ktrue"], p["scale"], p["bias"], B.CH_COL)
+                _, h = B.bnn_xnor_gemm_epilogue(rows, p["wp"], p["ktrue"], p["scale"], p["bias"], B.CH_COL,
+                                                out_y=b["y"])
             elif L.kind == "fc_f32":
                 h = B.bnn_fc_f32(h.view(self.batch, -1), p["w"], p["bias"], sign_input=True, out=b["y"])
             else:

@@ -559,6 +559,29 @@ def test_cfg4_fused_stack_small_batch_every_layer(reading):
     assert np.array_equal(host(out), ref["out"])
 
 
+def test_cfg4_fused_stack_graph_replays_match_oracle():
+    """The fused pass captured into a HIP graph: every replay (new input contents each time,
+    eager work and synchronisations of this process in between) must give the oracle's result
+    for the input it ran on."""
+    print("cfg4 fused stack, graph replays", flush=True)
+    from paper_1911_04477_amd.stack import VggStackFused
+    batch = 4
+    d = inputs.cfg4(batch=batch)
+    net = VggStackFused(d["layers"], d["params"], batch=batch, device=DEV)
+    xbuf = dev(d["x"]).clone()
+    net.capture(xbuf)
+    rng = np.random.default_rng(5)
+    for rep in range(4):
+        x = d["x"] if rep == 0 else rng.standard_normal(d["x"].shape).astype(np.float32)
+        xbuf.copy_(dev(x))
+        got = host(net.replay()).copy()
+        ref = oracle.vgg_stack(x, d["layers"], d["params"])["out"]
+        assert np.array_equal(got, ref), f"replay {rep}"
+        # eager work between replays: the same pass outside the graph, and an unrelated GEMM
+        assert np.array_equal(host(net.forward(xbuf)), ref), f"eager pass after replay {rep}"
+        _gemm_case(9, 70, 200, seed=rep)
+
+
 def test_cfg4_fused_stack_full_batch_sampled_images():
     print("cfg4 fused stack batch 256", flush=True)
     from paper_1911_04477_amd.stack import VggStack, VggStackFused
