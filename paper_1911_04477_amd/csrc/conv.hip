@@ -151,8 +151,7 @@ __global__ __launch_bounds__(256) void conv2d_f32_sign_kernel(const float *__res
 //                         pixel 32*b + l%32
 // A workgroup stages the filter taps of up to 128 channels in LDS ([tap][channel], odd row
 // stride), then each wave walks over its pixel groups: 27 clamped loads per lane, four channel
-// groups x 27 matrix instructions, and the affine map + sign on the vector unit (which runs
-// beside the matrix unit of the other resident waves).
+// groups x 27 matrix instructions, and the affine map + sign on the vector unit.
 constexpr int C1M_CH = 128;   // channels per workgroup (blockIdx.y)
 constexpr int C1M_RS = 129;   // LDS row stride of the tap-major filter tile
 typedef float c1m_v32f __attribute__((ext_vector_type(32)));
