@@ -338,7 +338,7 @@ def small_batch_latency(args):
 
 
 def mfma_ablation():
-    """The int8-MFMA-on-0/1 ablation beside the VALU GEMM on the GEMM view of cfg 5a and cfg 3."""
+    """The int8 and fp4 MFMA-on-0/1 ablations beside the VALU GEMM on the GEMM view of cfg 5a and cfg 3."""
     import torch
     from paper_1911_04477_amd import binding as B
     dev = "cuda:0"
@@ -350,13 +350,17 @@ def mfma_ablation():
         Bm = torch.randint(-2**62, 2**62, (N, Kw), dtype=torch.int64, device=dev)
         C = torch.empty((M, N), dtype=torch.int32, device=dev)
         C2 = torch.empty((M, N), dtype=torch.int32, device=dev)
+        C3 = torch.empty((M, N), dtype=torch.int32, device=dev)
         tv, _ = time_steps(lambda: B.bnn_xnor_gemm(A, Bm, K, C), 200, 100)
         tm, _ = time_steps(lambda: B.bnn_xnor_gemm_mfma_i8(A, Bm, K, C2), 200, 100)
+        t4, _ = time_steps(lambda: B.bnn_xnor_gemm_mfma_fp4(A, Bm, K, C3), 200, 100)
         bops = 2.0 * M * N * K
         out[name] = {"valu_TBOPS": round(bops / (tv / 200) / 1e12, 1), "mfma_i8_TBOPS": round(bops / (tm / 200) / 1e12, 1),
-                     "bit_identical": bool((C == C2).all().item()),
-                     "mfma_i8_frac_of_int8_dense_peak": round(bops / (tm / 200) / 5.0e15, 4)}
-        del A, Bm, C, C2
+                     "mfma_fp4_TBOPS": round(bops / (t4 / 200) / 1e12, 1),
+                     "bit_identical": bool((C == C2).all().item() and (C == C3).all().item()),
+                     "mfma_i8_frac_of_int8_dense_peak": round(bops / (tm / 200) / 5.0e15, 4),
+                     "mfma_fp4_frac_of_fp4_dense_peak": round(bops / (t4 / 200) / 10.1e15, 4)}
+        del A, Bm, C, C2, C3
     return out
 
 

@@ -40,7 +40,7 @@
  * ----------------------------------------------------------------------
  *  Every limit is checked on the host.  They follow from 32-bit indices inside the kernels:
  *   - GEMM entry points: M, N, K below 2^31; operand A at most 4 GiB (M * lda * 8 bytes).
- *     The MFMA ablation: K below 2^29.
+ *     The MFMA ablations: K below 2^29 (int8), below 2^24 (fp4).
  *   - Convolutions: N*H*W below 2^31 pixels; N*C*H*W at most 2^33 values; N*OH*OW at most
  *     2^29 output pixels; N*OH*OW*bnn_conv_kwords() below 2^31 words; kH*kW at most 32767;
  *     the packed filter bank at most 4 GiB; D*N*OH*OW at most 2^34 outputs; the packed
@@ -259,6 +259,17 @@ BNN_API bnn_status bnn_fc_f32(const float *x, const float *w, const float *bias,
 BNN_API bnn_status bnn_xnor_gemm_mfma_i8(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb,
                                  int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K,
                                  void *stream);
+
+/*
+ * bnn_xnor_gemm_mfma_fp4 -- the same ABLATION on the 4-bit floating-point matrix instruction
+ * (V_MFMA_SCALE_F32_32X32X64_F8F6F4, both operands E2M1): every packed bit becomes the code for
+ * 0.0 or 0.5, both operands carry the block scale 2, and the fp32 accumulator counts the
+ * positions where both are +1 exactly.  Same arguments, same bit-identical int32 result;
+ * K below 2^24 (BNN_ERR_UNSUPPORTED beyond).  Not used by any other entry point.
+ */
+BNN_API bnn_status bnn_xnor_gemm_mfma_fp4(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb,
+                                          int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K,
+                                          void *stream);
 
 /* ---- control group --------------------------------------------------------------------- */
 

@@ -31,6 +31,7 @@ SIGNATURES = {
     "bnn_im2col_workspace_bytes": (_sz, [_i32] * 10),
     "bnn_xnor_gemm": (_i32, [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _p]),
     "bnn_xnor_gemm_mfma_i8": (_i32, [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _p]),
+    "bnn_xnor_gemm_mfma_fp4": (_i32, [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _p]),
     "bnn_control_conv2d_f32": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p]),
     "bnn_xnor_gemm_epilogue": (_i32, [_p, _i64, _p, _i64, _i64, _i64, _i64, _p, _i64, _p, _i64, _p, _p, _i32, _p]),
     "bnn_conv2d": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p, _p, _p, _p, _sz, _p]),
@@ -173,6 +174,20 @@ def bnn_xnor_gemm_mfma_i8(A: torch.Tensor, B: torch.Tensor, K: int, C: Optional[
     ldb = B.stride(0) if N > 1 else max(B.shape[1], 1)
     _check(lib().bnn_xnor_gemm_mfma_i8(_ptr(A), lda, _ptr(B), ldb, _ptr(C), C.stride(0) if M > 1 else max(N, 1), M, N,
                                        K, _stream()), "bnn_xnor_gemm_mfma_i8")
+    return C
+
+
+def bnn_xnor_gemm_mfma_fp4(A: torch.Tensor, B: torch.Tensor, K: int, C: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Ablation: same contract as bnn_xnor_gemm, computed with the 4-bit floating-point MFMA."""
+    _dev(A, torch.int64, "A")
+    _dev(B, torch.int64, "B")
+    M, N = A.shape[0], B.shape[0]
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    lda = A.stride(0) if M > 1 else max(A.shape[1], 1)
+    ldb = B.stride(0) if N > 1 else max(B.shape[1], 1)
+    _check(lib().bnn_xnor_gemm_mfma_fp4(_ptr(A), lda, _ptr(B), ldb, _ptr(C), C.stride(0) if M > 1 else max(N, 1), M, N,
+                                        K, _stream()), "bnn_xnor_gemm_mfma_fp4")
     return C
 
 

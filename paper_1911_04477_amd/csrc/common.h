@@ -23,7 +23,8 @@ enum KernelId : int {
   KID_CONV_F32_SIGN = 11,
   KID_XNOR_GEMM_MFMA = 12,
   KID_CONTROL_CONV_F32 = 13,
-  KID_COUNT = 14
+  KID_XNOR_GEMM_MFMA_FP4 = 14,
+  KID_COUNT = 15
 };
 
 // Timing hook: records an event pair around a launch when profiling is on.

@@ -203,13 +203,15 @@ def test_glue_errors(L):
 
 
 def test_ablation_and_control_errors(L):
-    mf = L.bnn_xnor_gemm_mfma_i8
-    assert mf(A16, 4, A16, 4, A16, 8, 8, 8, 0, None) == SHAPE          # K = 0
-    assert mf(A16, 1, A16, 4, A16, 8, 8, 8, 200, None) == STRIDE       # lda < words
-    assert mf(A16, 4, A16, 4, A16, 4, 8, 8, 200, None) == STRIDE       # ldc < N
-    assert mf(A16, 4, A16, 4, None, 8, 8, 8, 200, None) == NULL
-    assert mf(A16, 4, MIS, 4, A16, 8, 8, 8, 200, None) == ALIGN
-    assert mf(None, 4, None, 4, None, 8, 0, 8, 200, None) == OK        # empty problem: nothing touched
+    for mf in (L.bnn_xnor_gemm_mfma_i8, L.bnn_xnor_gemm_mfma_fp4):
+        assert mf(A16, 4, A16, 4, A16, 8, 8, 8, 0, None) == SHAPE          # K = 0
+        assert mf(A16, 1, A16, 4, A16, 8, 8, 8, 200, None) == STRIDE       # lda < words
+        assert mf(A16, 4, A16, 4, A16, 4, 8, 8, 200, None) == STRIDE       # ldc < N
+        assert mf(A16, 4, A16, 4, None, 8, 8, 8, 200, None) == NULL
+        assert mf(A16, 4, MIS, 4, A16, 8, 8, 8, 200, None) == ALIGN
+        assert mf(None, 4, None, 4, None, 8, 0, 8, 200, None) == OK        # empty problem: nothing touched
+    # the fp4 form counts in fp32: reductions of 2^24 bits and more are refused
+    assert L.bnn_xnor_gemm_mfma_fp4(A16, 1 << 18, A16, 1 << 18, A16, 8, 8, 8, 1 << 24, None) == UNSUPPORTED
     cc = L.bnn_control_conv2d_f32
     assert cc(A16, A16, 2, 3, 8, 8, 4, 9, 9, 1, 1, 0, 0, A16, None) == SHAPE   # kernel larger than image
     assert cc(A16, A16, 2, 3, 8, 8, -1, 3, 3, 1, 1, 1, 1, A16, None) == SHAPE

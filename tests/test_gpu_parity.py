@@ -599,15 +599,17 @@ def test_cfg4_fused_stack_full_batch_sampled_images():
 
 # ---------------------------------------------------------------- MFMA ablation
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (37, 150, 300), (128, 128, 64), (130, 257, 1152), (64, 64, 256),
-                                   (200, 333, 2304 + 17), (5, 700, 63)])
+                                   (200, 333, 2304 + 17), (5, 700, 63),
+                                   (300, 3300, 200), (513, 1650, 127)])
 def test_mfma_ablation_matches_oracle(M, N, K):
     print(f"mfma M={M} N={N} K={K}", flush=True)
     rng = np.random.default_rng(M * 7919 + N * 31 + K)
     A = inputs.inject_specials(rng.standard_normal((M, K)).astype(np.float32), 1, frac=0.002)
     Bm = inputs.inject_specials(rng.standard_normal((N, K)).astype(np.float32), 2, frac=0.002)
     Ap, Bp = B.bnn_encode(dev(A)), B.bnn_encode(dev(Bm))
-    got = host(B.bnn_xnor_gemm_mfma_i8(Ap, Bp, K))
-    assert np.array_equal(got, oracle.gemm_pm1(A, Bm))
+    ref = oracle.gemm_pm1(A, Bm)
+    assert np.array_equal(host(B.bnn_xnor_gemm_mfma_i8(Ap, Bp, K)), ref)
+    assert np.array_equal(host(B.bnn_xnor_gemm_mfma_fp4(Ap, Bp, K)), ref)
 
 
 def test_mfma_ablation_equals_valu_path_at_cfg2():
@@ -617,6 +619,7 @@ def test_mfma_ablation_equals_valu_path_at_cfg2():
     a = host(B.bnn_xnor_gemm_mfma_i8(Ap, Wp, inputs.CFG2.K))
     b = host(B.bnn_xnor_gemm(Ap, Wp, inputs.CFG2.K))
     assert np.array_equal(a, b)
+    assert np.array_equal(host(B.bnn_xnor_gemm_mfma_fp4(Ap, Wp, inputs.CFG2.K)), b)
 
 
 # ---------------------------------------------------------------- fp32 control group (section 4.4)
