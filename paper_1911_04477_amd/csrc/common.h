@@ -100,6 +100,7 @@ struct GemmParams {
   FastDiv divOHW;
   int64_t img_stride;  // elements between images in C / Y
   int tilesM, tilesN;
+  int prio_from;       // workgroups with id >= prio_from lower their wave priority as they advance through K
   ConvGeom g;          // implicit B only
   uint64_t *outp;      // packed-sign output [pixels, cw_out] (packed epilogue only)
   int cw_out;

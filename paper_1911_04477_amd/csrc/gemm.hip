@@ -446,7 +446,27 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   // here; the wait names every loaded SGPR as in/out operand, which orders all uses after
   // it.  The latency of one wave's loads is covered by the other waves on the SIMD.
   const int nfast = nfull + (window ? 1 : 0);
+  // Wave priority.  The instruction arbiter prefers older waves, so of the workgroups resident
+  // on a compute unit the oldest runs at nearly full speed, the others in its gaps, and they
+  // finish one after the other; the last one then runs alone, at an occupancy where neither its
+  // latencies nor the yield slots of its pairs are filled.  The workgroups of the last resident
+  // set (ids >= prio_from) therefore lower their priority from 3 to 0 as they advance through
+  // K: whoever is behind gets the issue slots, and they finish within an eighth of K of each other.  Earlier workgroups keep priority 3 and free their slot as early as before.
+  const bool paced = (int)blockIdx.x >= p.prio_from;
+  int prio_cur = 3;
+  __builtin_amdgcn_s_setprio(3);
   for (int c = 0; c < nfast; ++c) {
+    if (paced) {
+      // steps at 1/2, 3/4 and 7/8 of K (wave-uniform): what is left after the last step is all
+      // a workgroup can have to do alone
+      const int lvl = (2 * c < nstages) ? 3 : (4 * c < 3 * nstages) ? 2 : (8 * c < 7 * nstages) ? 1 : 0;
+      if (lvl != prio_cur) {
+        prio_cur = lvl;
+        if (lvl == 2) __builtin_amdgcn_s_setprio(2);
+        else if (lvl == 1) __builtin_amdgcn_s_setprio(1);
+        else __builtin_amdgcn_s_setprio(0);
+      }
+    }
     const int buf = c & 1;
     const bool more = c + 1 < nstages;
     if (more) stage_load(c + 1);
@@ -794,6 +814,10 @@ __global__ __launch_bounds__(256) void xnor_gemm_direct_kernel(GemmParams p) {
 template <int TN, int WM, int WN, int MINW, int BMODE, int EMODE, int YIELD>
 static bnn_status launch_one(GemmParams &p, hipStream_t s, int kid) {
   using Cfg = GemmCfg<TN, WM, WN>;
+  // the last resident set: MINW waves per SIMD, 4 SIMDs, 256 compute units
+  const int64_t resident = (int64_t)(MINW * 4 / (Cfg::THREADS / 64)) * 256;
+  const int64_t nb = (int64_t)p.tilesM * p.tilesN;
+  p.prio_from = (int)(nb > resident ? nb - resident : 0);
   ProfScope ps(kid, s);
   hipLaunchKernelGGL((xnor_gemm_kernel<TN, WM, WN, MINW, BMODE, EMODE, YIELD>),
                      dim3((unsigned)(p.tilesM * p.tilesN)), dim3(Cfg::THREADS), 0, s, p);
