@@ -451,7 +451,8 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   // finish one after the other; the last one then runs alone, at an occupancy where neither its
   // latencies nor the yield slots of its pairs are filled.  The workgroups of the last resident
   // set (ids >= prio_from) therefore lower their priority from 3 to 0 as they advance through
-  // K: whoever is behind gets the issue slots, and they finish within an eighth of K of each other.  Earlier workgroups keep priority 3 and free their slot as early as before.
+  // K: whoever is behind gets the issue slots, and they finish within an eighth of K of each
+  // other.  Earlier workgroups keep priority 3 and free their slot as early as before.
   const bool paced = (int)blockIdx.x >= p.prio_from;
   int prio_cur = 3;
   __builtin_amdgcn_s_setprio(3);
