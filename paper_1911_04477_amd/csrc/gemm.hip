@@ -174,6 +174,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   __shared__ __attribute__((aligned(16))) uint32_t sB[2 * Cfg::TILE];
   __shared__ uint2 sTab[BMODE == 2 ? 2 * LEAN_MAX_STAGES : 1];
 
+  __builtin_amdgcn_s_setprio(3);  // prologue and epilogue are short and latency-bound: let them through
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -450,17 +451,22 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   // on a compute unit the oldest runs at nearly full speed, the others in its gaps, and they
   // finish one after the other; the last one then runs alone, at an occupancy where neither its
   // latencies nor the yield slots of its pairs are filled.  The workgroups of the last resident
-  // set (ids >= prio_from) therefore lower their priority from 3 to 0 as they advance through
-  // K: whoever is behind gets the issue slots, and they finish within an eighth of K of each
-  // other.  Earlier workgroups keep priority 3 and free their slot as early as before.
+  // set (ids >= prio_from) therefore lower their priority as they advance through K: whoever is
+  // behind gets the issue slots, and they finish within an eighth of K of each other.  Earlier
+  // workgroups keep one priority and free their slot as early as before.
   const bool paced = (int)blockIdx.x >= p.prio_from;
-  int prio_cur = 3;
-  __builtin_amdgcn_s_setprio(3);
+  // Prologue and store run at priority 3 (set at kernel entry and before the store): they are
+  // short and latency-bound, and a new workgroup that gets through its prologue quickly is one
+  // more set of waves with work to issue.  The K loop runs below that: at 2 for the earlier
+  // workgroups, stepping down from 2 for the paced ones (from 3 when every workgroup of the
+  // launch is paced, so that the steps at 1/2, 3/4 and 7/8 of K all exist).
+  const int prio_top = p.prio_from == 0 ? 3 : 2;
+  int prio_cur = prio_top;
+  if (prio_top == 2) __builtin_amdgcn_s_setprio(2);
   for (int c = 0; c < nfast; ++c) {
     if (paced) {
-      // steps at 1/2, 3/4 and 7/8 of K (wave-uniform): what is left after the last step is all
-      // a workgroup can have to do alone
-      const int lvl = (2 * c < nstages) ? 3 : (4 * c < 3 * nstages) ? 2 : (8 * c < 7 * nstages) ? 1 : 0;
+      const int steps = (2 * c < nstages) ? 0 : (4 * c < 3 * nstages) ? 1 : (8 * c < 7 * nstages) ? 2 : 3;
+      const int lvl = max(prio_top - steps, 0);  // wave-uniform
       if (lvl != prio_cur) {
         prio_cur = lvl;
         if (lvl == 2) __builtin_amdgcn_s_setprio(2);
@@ -589,6 +595,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   }
 
   // ---- store ------------------------------------------------------------------------
+  __builtin_amdgcn_s_setprio(3);
   if constexpr (EMODE == 0) {
     store_tile<TN>(acc, m0, n0 + wn * 64 * TN + lane);
   } else {
