@@ -913,7 +913,10 @@ bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s) {
     // tiles the packed epilogue is written for: 64 x 256 (3), 64 x 128 (6), 32 x 256 (1), 32 x 128 (4);
     // pooling needs four columns per lane (3 or 1)
     const bool ok = p.g.pool ? (cfg == 3 || cfg == 1) : (cfg == 3 || cfg == 6 || cfg == 1 || cfg == 4);
-    if (!ok) cfg = 3;  // 64 x 256: fastest at every layer shape measured
+    // 64 x 256 is the fastest tile when a compute unit gets more than two of them; with two or
+    // fewer, 32 x 256 (four waves per workgroup, twice as many workgroups) is as fast or faster
+    const int64_t t256 = (int64_t)((p.M + 63) / 64) * ((p.N + 255) / 256);
+    if (!ok) cfg = t256 <= 512 ? 1 : 3;
   }
   if (cfg < 0) {
     // Measured on MI355X: 64 x 256 (TN = 4, eight waves per workgroup, six per SIMD) is the
