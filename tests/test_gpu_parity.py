@@ -559,6 +559,23 @@ def test_cfg4_fused_stack_small_batch_every_layer(reading):
     assert np.array_equal(host(out), ref["out"])
 
 
+def test_cfg4_fused_stack_full_batch_is_deterministic():
+    """Twenty passes at the benchmark's batch size give the same bits every time, layer by layer
+    (a race between waves would show up as a difference between passes)."""
+    print("cfg4 fused stack batch 256, repeated passes", flush=True)
+    from paper_1911_04477_amd.stack import VggStackFused
+    d = inputs.cfg4(batch=256)
+    net = VggStackFused(d["layers"], d["params"], batch=256, device=DEV)
+    x = dev(d["x"])
+    out0, acts0 = net.forward(x, keep=True)
+    torch.cuda.synchronize()
+    for rep in range(20):
+        out, acts = net.forward(x, keep=True)
+        for i, (a, b) in enumerate(zip(acts0, acts)):
+            assert torch.equal(a, b), f"pass {rep}, layer {i}"
+        assert torch.equal(out0, out), f"pass {rep}"
+
+
 def test_cfg4_fused_stack_graph_replays_match_oracle():
     """The fused pass captured into a HIP graph: every replay (new input contents each time,
     eager work and synchronisations of this process in between) must give the oracle's result
