@@ -212,11 +212,13 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   const uint64_t Abase0 = ((uint64_t)Abase_hi << 32) | (uint64_t)Abase_lo;
   const cu32_ptr Ac = (cu32_ptr)(uintptr_t)p.A;
 
+  // Zeroed through an opaque statement: a plain "= 0" is re-materialised by the compiler on
+  // every path into the loop (the accumulators were cleared twice per tile).
   int acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) acc[i][j] = 0;
+    for (int j = 0; j < TN; ++j) asm volatile("v_mov_b32 %0, 0" : "=v"(acc[i][j]));
 
   // K bookkeeping (all wave-uniform).  Full chunks cover words [0, 4*nfull).  Two words left
   // over are done by a half chunk; one or three by a last "window" chunk over words
