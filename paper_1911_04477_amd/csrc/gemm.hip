@@ -325,7 +325,10 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   auto stage_load = [&](int s) {
     const int wbase = stage_word0(s);
     if constexpr (BMODE == 2) {
-      const uint2 ent = sTab[2 * s + my_piece];
+      // one 8-byte LDS read (through a 64-bit value: read as two words, the compiler fetches the
+      // second only for valid taps, behind a branch)
+      const uint64_t ent64 = *reinterpret_cast<const volatile uint64_t *>(&sTab[2 * s + my_piece]);
+      const uint2 ent = make_uint2((uint32_t)ent64, (uint32_t)(ent64 >> 32));
       const uint32_t my_off = ent.x & ~15u;
       const char *base = reinterpret_cast<const char *>(p.g.act);
 #pragma unroll
