@@ -322,6 +322,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   // stage_load only ISSUES the global loads (raw words stay in registers, nothing uses them
   // until stage_store a whole chunk of compute later), so their latency is never waited on.
   u32x4 stage[PPT];
+  uint32_t staged_flags = 0;  // lean gather: flags of the table entry the last stage_load used
   auto stage_load = [&](int s) {
     const int wbase = stage_word0(s);
     if constexpr (BMODE == 2) {
@@ -329,6 +330,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
       // second only for valid taps, behind a branch)
       const uint64_t ent64 = *reinterpret_cast<const volatile uint64_t *>(&sTab[2 * s + my_piece]);
       const uint2 ent = make_uint2((uint32_t)ent64, (uint32_t)(ent64 >> 32));
+      staged_flags = ent.x;  // stage_store(s) selects the pad word by the same entry
       const uint32_t my_off = ent.x & ~15u;
       const char *base = reinterpret_cast<const char *>(p.g.act);
 #pragma unroll
@@ -406,7 +408,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
     if constexpr (BMODE == 2) {
       // pad words: all ones, except the last word of a tap (low C % 64 bits) and words past K (0);
       // rows hold whole words, so there is no tail mask
-      const uint32_t fl = sTab[2 * s + my_piece].x;
+      const uint32_t fl = staged_flags;
       const uint64_t last = pad_word64(p.g.C, p.g.Cw - 1);
       const uint32_t a1 = (fl & LEAN_LIVE) ? 0xffffffffu : 0u;
       const bool te = (fl & LEAN_TAP_END) != 0u;
