@@ -326,10 +326,9 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   auto stage_load = [&](int s) {
     const int wbase = stage_word0(s);
     if constexpr (BMODE == 2) {
-      // one 8-byte LDS read (through a 64-bit value: read as two words, the compiler fetches the
-      // second only for valid taps, behind a branch)
-      const uint64_t ent64 = *reinterpret_cast<const volatile uint64_t *>(&sTab[2 * s + my_piece]);
-      const uint2 ent = make_uint2((uint32_t)ent64, (uint32_t)(ent64 >> 32));
+      // (both words are used unconditionally, the flags by stage_store: one 8-byte LDS read; when
+      // only the offset depended on it the compiler fetched it behind a branch, for valid taps only)
+      const uint2 ent = sTab[2 * s + my_piece];
       staged_flags = ent.x;  // stage_store(s) selects the pad word by the same entry
       const uint32_t my_off = ent.x & ~15u;
       const char *base = reinterpret_cast<const char *>(p.g.act);
