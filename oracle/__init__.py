@@ -263,6 +263,11 @@ def pack_fc_weight_nhwc(w, C: int, H: int, W: int) -> np.ndarray:
 # The VGG-small stack as a composition of the definitions above.
 # Block order: conv -> int32 -> (2x2 max-pool on int32 if pooled) -> fma(scale, acc,
 # bias) -> sign taken by the next binarized layer.  Flatten order is NCHW.
+# Pinned (tests/test_oracle_pins.py) on a five-layer table with small-integer data
+# against a float64 composition of torch CPU routines (conv2d on +-1 tensors padded
+# with +1, max_pool2d, affine, NCHW reshape, x >= 0), which is exact there; the case
+# fails for affine-before-pool (negative scales), an NHWC flatten or a missing sign
+# before the classifier.
 # ----------------------------------------------------------------------------
 def vgg_stack(x, layers: Sequence, params: Sequence[Dict[str, np.ndarray]]) -> Dict[str, object]:
     acts: List[np.ndarray] = []

@@ -477,3 +477,134 @@ def test_gemm_refuses_k_beyond_exact_fp32_range():
         oracle.gemm_pm1(a, a)
     k = (1 << 24) - 1
     assert oracle.gemm_pm1(a[:, :k], a[:, :k])[0, 0] == k
+
+
+# ---- the stack composition (the network of section 4.2, bias / reshape steps of section 2.2) ----
+def _tiny_stack(seed=4477):
+    """A five-layer table with every block kind, on small integers and dyadic scale / bias so
+    that every fp32 operation of the oracle is exact and float64 library routines must agree
+    to the bit: real-valued conv 2->4 at 4x4, pooled binarized conv 4->6 (scales of both
+    signs), unpooled binarized conv 6->5 at 2x2, binarized FC 20->7, real-valued classifier 7->3."""
+    L = inputs.StackLayer
+    layers = [L("conv_f32", 2, 4, 4), L("bconv", 4, 6, 4, pool=True), L("bconv", 6, 5, 2, pool=False),
+              L("bfc", 20, 7), L("fc_f32", 7, 3)]
+    g = torch.Generator().manual_seed(seed)
+
+    def ints(shape, lo, hi):
+        return torch.randint(lo, hi + 1, shape, generator=g).float().numpy()
+
+    def dyadic(n, signs):
+        mag = torch.tensor([0.5, 1.0, 1.5, 2.0])[torch.randint(0, 4, (n,), generator=g)]
+        sg = torch.tensor(signs)[torch.randint(0, len(signs), (n,), generator=g)]
+        return (mag * sg).numpy().astype(np.float32)
+
+    def half_ints(n):
+        return (torch.randint(-5, 6, (n,), generator=g).float() * 0.5).numpy()
+
+    x = ints((3, 2, 4, 4), -4, 4)
+    params = [
+        {"w": ints((4, 2, 3, 3), -3, 3), "scale": dyadic(4, [1.0, -1.0]), "bias": half_ints(4)},
+        {"w": ints((6, 4, 3, 3), -3, 3), "scale": np.array([-1.5, 0.5, -0.5, 2.0, -1.0, 1.0], np.float32),
+         "bias": half_ints(6)},
+        {"w": ints((5, 6, 3, 3), -3, 3), "scale": dyadic(5, [1.0, -1.0]), "bias": half_ints(5)},
+        {"w": ints((7, 20), -3, 3), "scale": dyadic(7, [1.0, -1.0]), "bias": half_ints(7)},
+        {"w": ints((3, 7), -6, 6), "bias": half_ints(3)},
+    ]
+    return x, layers, params
+
+
+def _stack_by_library_routines(x, layers, params, mutate=None):
+    """The same network out of torch CPU float64 routines, written without the oracle:
+    conv2d on +-1 tensors padded with +1, max_pool2d, broadcast affine map, reshape in NCHW
+    order, where(x >= 0).  `mutate` plants one mistake (used to show that the comparison
+    notices it)."""
+    t = lambda a: torch.from_numpy(np.asarray(a)).double()
+    pm1 = lambda a: torch.where(a >= 0, 1.0, -1.0).double()
+    ch = lambda v: t(v)[None, :, None, None]
+    h = t(x)
+    acts = []
+    for L, p in zip(layers, params):
+        if L.kind == "conv_f32":
+            h = F.conv2d(h, t(p["w"]), padding=1) * ch(p["scale"]) + ch(p["bias"])
+        elif L.kind == "bconv":
+            padded = F.pad(pm1(h), (1, 1, 1, 1), value=1.0)  # zero-pad before the sign: pads are +1
+            acc = F.conv2d(padded, pm1(t(p["w"])))
+            if L.pool and mutate == "affine_before_pool":
+                h = F.max_pool2d(acc * ch(p["scale"]) + ch(p["bias"]), 2)
+            else:
+                if L.pool:
+                    acc = F.max_pool2d(acc, 2)
+                h = acc * ch(p["scale"]) + ch(p["bias"])
+        elif L.kind == "bfc":
+            s = pm1(h)
+            flat = s.permute(0, 2, 3, 1).reshape(s.shape[0], -1) if mutate == "nhwc_flatten" else s.reshape(s.shape[0], -1)
+            h = (flat @ pm1(t(p["w"])).T) * t(p["scale"])[None, :] + t(p["bias"])[None, :]
+        elif L.kind == "fc_f32":
+            xin = h if mutate == "no_final_sign" else pm1(h)
+            h = xin.reshape(h.shape[0], -1) @ t(p["w"]).T + t(p["bias"])[None, :]
+        acts.append(h.numpy())
+    return acts
+
+
+def test_vgg_stack_composition_against_library_routines():
+    """Pins the block order of the stack: conv -> max-pool on the integers -> affine -> sign, NCHW
+    flatten into the binarized FC, sign before the real-valued classifier.  Every activation must
+    equal the float64 composition bit for bit, and the case is sensitive to each of the three
+    plausible mistakes (affine before pool with a negative scale, NHWC flatten, missing last sign)."""
+    x, layers, params = _tiny_stack()
+    got = oracle.vgg_stack(x, layers, params)
+    ref = _stack_by_library_routines(x, layers, params)
+    assert len(got["acts"]) == len(ref) == 5
+    for i, (a, r) in enumerate(zip(got["acts"], ref)):
+        assert a.shape == r.shape and a.dtype == np.float32
+        assert np.array_equal(a.astype(np.float64), r), f"layer {i} ({layers[i].kind})"
+    assert np.array_equal(got["out"], got["acts"][-1])
+    # shapes: pooled block halves the map, the FC sees 5 * 2 * 2 values
+    assert [a.shape for a in got["acts"]] == [(3, 4, 4, 4), (3, 6, 2, 2), (3, 5, 2, 2), (3, 7), (3, 3)]
+    # the case notices each planted mistake at the first layer it touches and at the output
+    for mut, first in (("affine_before_pool", 1), ("nhwc_flatten", 3), ("no_final_sign", 4)):
+        bad = _stack_by_library_routines(x, layers, params, mutate=mut)
+        for i in range(first):
+            assert np.array_equal(bad[i], ref[i])
+        assert not np.array_equal(bad[first], ref[first]), mut
+        assert not np.array_equal(bad[-1], ref[-1]), mut
+        # ... and what flips are signs the next layer consumes, not only magnitudes
+        if first < 4:
+            assert np.any((bad[first] >= 0) != (ref[first] >= 0)), mut
+
+
+def test_vgg_stack_mistakes_in_the_oracle_are_caught(monkeypatch):
+    """The same three mistakes planted in the oracle's own composition make the comparison fail."""
+    x, layers, params = _tiny_stack()
+    ref = _stack_by_library_routines(x, layers, params)
+
+    def differs():
+        got = oracle.vgg_stack(x, layers, params)["acts"]
+        return any(not np.array_equal(a.astype(np.float64), r) for a, r in zip(got, ref))
+
+    assert not differs()
+    real_pool, real_affine, real_fc, real_gemm = (oracle.maxpool2x2_i32, oracle.scale_bias, oracle.fc_f32_seq,
+                                                  oracle.gemm_pm1)
+    # (1) affine first, pool afterwards on the fp32 map
+    with monkeypatch.context() as m:
+        m.setattr(oracle, "maxpool2x2_i32", lambda a: a)
+
+        def affine_then_pool(acc, s, b, axis):
+            y = real_affine(acc, s, b, axis)
+            if axis == "nchw" and y.shape[-1] == 4:  # the pooled block's 4x4 map
+                y = y.reshape(y.shape[0], y.shape[1], 2, 2, 2, 2).max(axis=(3, 5))
+            return y
+        m.setattr(oracle, "scale_bias", affine_then_pool)
+        assert differs()
+    # (2) NHWC flatten into the binarized FC
+    with monkeypatch.context() as m:
+        def gemm_nhwc(a, w):
+            a4 = a.reshape(a.shape[0], 5, 2, 2).transpose(0, 2, 3, 1).reshape(a.shape[0], -1)
+            return real_gemm(a4, w)
+        m.setattr(oracle, "gemm_pm1", gemm_nhwc)
+        assert differs()
+    # (3) the classifier fed the real values instead of their signs
+    with monkeypatch.context() as m:
+        m.setattr(oracle, "fc_f32_seq", lambda xx, w, b=None, sign_input=False: real_fc(xx, w, b, sign_input=False))
+        assert differs()
+    assert oracle.maxpool2x2_i32 is real_pool and not differs()
