@@ -18,6 +18,8 @@
  *    is launched.  A failed launch is reported as BNN_ERR_HIP.
  *  - Empty problems (a zero row / column / batch count) return BNN_OK without a
  *    launch.  A reduction length K <= 0 is BNN_ERR_SHAPE.
+ *  - What a call computes and which kernels it launches depend on its arguments and the
+ *    device only: the library keeps no settings between calls.
  *
  * Packed format (part of the ABI; section 3.1: value -1 <-> bit 0, +1 <-> bit 1)
  * -----------------------------------------------------------------------------
@@ -39,7 +41,7 @@
  * Implemented range (BNN_ERR_UNSUPPORTED beyond it; nothing is launched)
  * ----------------------------------------------------------------------
  *  Every limit is checked on the host.  They follow from 32-bit indices inside the kernels:
- *   - GEMM entry points: M, N, K below 2^31; operand A at most 4 GiB (M * lda * 8 bytes).
+ *   - GEMM entry points: M, K below 2^31, N at most 2^31 - 257; operand A at most 4 GiB (M * lda * 8 bytes).
  *     The MFMA ablations: K below 2^29 (int8), below 2^24 (fp4).
  *   - Convolutions: N*H*W below 2^31 pixels; N*C*H*W at most 2^33 values; N*OH*OW at most
  *     2^29 output pixels; N*OH*OW*bnn_conv_kwords() below 2^31 words; kH*kW at most 32767;
@@ -58,7 +60,7 @@
 #include <stdint.h>
 
 /* The library is built with hidden default visibility; only what is declared here (and the
- * test hooks of bnn_testing.h) is exported. */
+ * test / measurement entry points of bnn_testing.h) is exported. */
 #define BNN_API __attribute__((visibility("default")))
 
 #ifdef __cplusplus
@@ -286,36 +288,6 @@ BNN_API bnn_status bnn_xnor_gemm_mfma_fp4(const uint64_t *A, int64_t lda, const 
 BNN_API bnn_status bnn_control_conv2d_f32(const float *x, const float *w, int N, int C, int H, int W,
                                   int D, int kH, int kW, int sH, int sW, int pH, int pW,
                                   float *out, void *stream);
-
-/* ---- measurement helpers ------------------------------------------------------------ */
-
-/*
- * Kernel timing.  While enabled, every kernel the library launches is bracketed by a
- * pair of HIP events recorded on the caller's stream (host objects, created on first
- * use and kept until bnn_prof_enable(0)).  At most BNN_PROF_MAX_RECORDS launches are
- * recorded between two resets; later ones run untimed.  Not thread-safe.
- */
-#define BNN_PROF_MAX_RECORDS 4096
-BNN_API bnn_status bnn_prof_enable(int enable);
-BNN_API bnn_status bnn_prof_reset(void);
-BNN_API int64_t bnn_prof_count(void);
-/* Synchronises on record i's end event, then returns its kernel id and duration. */
-BNN_API bnn_status bnn_prof_get(int64_t i, int *kernel_id, float *milliseconds);
-BNN_API const char *bnn_kernel_name(int kernel_id);
-
-/*
- * bnn_valu_peak_probe -- a microbenchmark, not part of the method: every lane runs
- * `iters` rounds of 64 independent xor + popcount-accumulate pairs from registers
- * (2 * 64 * iters VALU lane-operations per lane) and the grid is `blocks` workgroups
- * of 256 threads.  sink [blocks*256] int32 receives a value that depends on all of them.
- */
-BNN_API bnn_status bnn_valu_peak_probe(int32_t *sink, int blocks, int iters, void *stream);
-
-/*
- * bnn_copy_probe -- plain device copy of n_bytes (multiple of 16) used as the yardstick
- * for achievable HBM bandwidth and for scaling hardware byte counters.
- */
-BNN_API bnn_status bnn_copy_probe(const void *src, void *dst, size_t n_bytes, void *stream);
 
 #ifdef __cplusplus
 }

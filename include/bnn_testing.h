@@ -1,8 +1,10 @@
 /*
- * bnn_testing.h -- switches for tests and measurements; NOT part of the library's ABI and
- * not meant for applications.  They set process-wide state and are not thread-safe; a test
- * that uses one restores the default afterwards.  None of them changes any result: every
- * kernel variant they select computes the values bnn.h specifies.
+ * bnn_testing.h -- entry points for tests and measurements; NOT part of the library's ABI and
+ * not meant for applications.  The *_testing_* calls are the calls of bnn.h with the kernel
+ * variant chosen by the caller instead of by the size heuristic; every variant computes the
+ * values bnn.h specifies, and nothing set here outlives the call.  Only the kernel-timing hook
+ * (bnn_prof_*) keeps state between calls: a list of HIP events, which never changes what a
+ * call computes or launches.
  */
 #ifndef BNN_TESTING_H_
 #define BNN_TESTING_H_
@@ -14,37 +16,72 @@ extern "C" {
 #endif
 
 /*
- * Force the tile configuration of the Xnor-Bitcount GEMM (section 3.2) instead of the size
- * heuristic, for bnn_xnor_gemm, bnn_xnor_gemm_epilogue, bnn_conv2d and bnn_conv2d_packed:
- *   -1  heuristic (default)
+ * Tile configurations of the Xnor-Bitcount GEMM (section 3.2), argument `cfg` below:
+ *   -1  the size heuristic (what bnn.h's entry points use)
  *    1  32 x 256 tile      2  32 x 64       3  64 x 256      4  32 x 128      6  64 x 128
  *    7  one wave per 8 x 64 tile, operand B read straight from memory (small problems)
  *    8  one wave per 8 x 128 tile, likewise
  *    9  as 7 with the reduction axis split over the four waves of a workgroup
- * A value that a call cannot use (the packed epilogue needs the 64 x 256 tile) is ignored
- * by that call.  Other values select the heuristic.
+ * A value that a call cannot use (the packed epilogue needs a 32- or 64-row tile with two or
+ * four column groups; 7 to 9 exist for an explicit B with int32 / fp32 output only) selects the
+ * heuristic for that call.
+ * `lean`: 1 = convolutions whose geometry allows it gather their patches with the table-driven
+ * loader (what bnn.h's entry points do); 0 = always the general loader.
  */
-BNN_API void bnn_internal_force_gemm_cfg(int cfg);
+
+/* bnn_xnor_gemm_epilogue (and, with Y == NULL, bnn_xnor_gemm) on tile configuration cfg. */
+BNN_API bnn_status bnn_testing_xnor_gemm_epilogue(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb,
+                                                  int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc, float *Y,
+                                                  int64_t ldy, const float *scale, const float *bias,
+                                                  bnn_ch_axis axis, int cfg, void *stream);
+
+/* bnn_conv2d on tile configuration cfg and gather `lean`. */
+BNN_API bnn_status bnn_testing_conv2d(const float *x, const uint64_t *w_packed, int N, int C, int H, int W, int D,
+                                      int kH, int kW, int sH, int sW, int pH, int pW, int32_t *out_i32,
+                                      float *out_f32, const float *scale, const float *bias, void *workspace,
+                                      size_t workspace_bytes, int cfg, int lean, void *stream);
+
+/* bnn_conv2d_packed on tile configuration cfg and gather `lean`. */
+BNN_API bnn_status bnn_testing_conv2d_packed(const uint64_t *x_packed, const uint64_t *w_packed, int N, int C, int H,
+                                             int W, int D, int kH, int kW, int sH, int sW, int pH, int pW, int pool,
+                                             int32_t *out_i32, float *out_f32, uint64_t *out_packed,
+                                             const float *scale, const float *bias, int cfg, int lean,
+                                             void *stream);
+
+/* ---- measurement helpers ------------------------------------------------------------ */
 
 /*
- * 1 (default): convolutions whose geometry allows it gather their patches with the
- * table-driven loader; 0: always the general loader.
+ * Kernel timing.  While enabled, every kernel the library launches is bracketed by a
+ * pair of HIP events recorded on the caller's stream (host objects, created on first
+ * use and kept until bnn_prof_enable(0)).  At most BNN_PROF_MAX_RECORDS launches are
+ * recorded between two resets; later ones run untimed.  Not thread-safe.
  */
-BNN_API void bnn_internal_lean_gather(int on);
+#define BNN_PROF_MAX_RECORDS 4096
+BNN_API bnn_status bnn_prof_enable(int enable);
+BNN_API bnn_status bnn_prof_reset(void);
+BNN_API int64_t bnn_prof_count(void);
+/* Synchronises on record i's end event, then returns its kernel id and duration. */
+BNN_API bnn_status bnn_prof_get(int64_t i, int *kernel_id, float *milliseconds);
+BNN_API const char *bnn_kernel_name(int kernel_id);
 
 /*
- * Selects what bnn_valu_peak_probe runs.  Each mode issues the same number of vector
- * lane-operations per launch for given (blocks, iters), so rates compare directly.
- *    0  (default) independent xor + popcount pairs, both operands in vector registers
- *    1  the GEMM's pattern: xor operand in a scalar register, each xor directly followed by
- *       the popcount that consumes it
- *    2  xor only;  3  popcount-accumulate only;  4  dependent pairs, vector operands
- *    5, 6  the GEMM's own row statements for 2 / 4 column groups per lane (with the yield)
- *    7, 8  the same without the yield
- *    9, 10 fp32 multiply-add chains, multiplier in a vector (9) / a scalar (10) register
- * Unknown values run mode 0.
+ * bnn_valu_peak_probe -- a microbenchmark, not part of the method: every lane issues
+ * 2 * 64 * iters vector lane-operations (xor + popcount-accumulate pairs) from registers,
+ * no loads; the grid is `blocks` workgroups of 256 threads.  sink [blocks*256] int32
+ * receives a value that depends on all of them.
+ *   kind 0  independent pairs, both operands in vector registers, scheduled by the compiler
+ *   kind 2 / 4  the GEMM's own row statements for 2 / 4 column groups per lane (xor operand
+ *           in a scalar register, each xor directly followed by its popcount, one-cycle
+ *           yield after each pair); iters should be a multiple of kind
+ * Other kinds: BNN_ERR_SHAPE.
  */
-BNN_API void bnn_internal_probe_mode(int mode);
+BNN_API bnn_status bnn_valu_peak_probe(int32_t *sink, int blocks, int iters, int kind, void *stream);
+
+/*
+ * bnn_copy_probe -- plain device copy of n_bytes (multiple of 16) used as the yardstick
+ * for achievable HBM bandwidth and for scaling hardware byte counters.
+ */
+BNN_API bnn_status bnn_copy_probe(const void *src, void *dst, size_t n_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -42,12 +42,21 @@ SIGNATURES = {
     "bnn_maxpool2x2": (_i32, [_p, _i32, _i32, _i32, _i32, _p, _p, _p, _p, _p]),
     "bnn_conv2d_f32": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p, _p, _p]),
     "bnn_fc_f32": (_i32, [_p, _p, _p, _i64, _i64, _i64, _i32, _p, _p]),
+}
+
+# include/bnn_testing.h: the same calls with the kernel variant chosen by the caller, the
+# kernel-timing hook and the two yardstick kernels.  Tests and bench.py only.
+TESTING_SIGNATURES = {
+    "bnn_testing_xnor_gemm_epilogue": (_i32, [_p, _i64, _p, _i64, _i64, _i64, _i64, _p, _i64, _p, _i64, _p, _p, _i32,
+                                              _i32, _p]),
+    "bnn_testing_conv2d": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p, _p, _p, _p, _sz, _i32, _i32, _p]),
+    "bnn_testing_conv2d_packed": (_i32, [_p, _p] + [_i32] * 12 + [_p, _p, _p, _p, _p, _i32, _i32, _p]),
     "bnn_prof_enable": (_i32, [_i32]),
     "bnn_prof_reset": (_i32, []),
     "bnn_prof_count": (_i64, []),
     "bnn_prof_get": (_i32, [_i64, ctypes.POINTER(_i32), ctypes.POINTER(ctypes.c_float)]),
     "bnn_kernel_name": (ctypes.c_char_p, [_i32]),
-    "bnn_valu_peak_probe": (_i32, [_p, _i32, _i32, _p]),
+    "bnn_valu_peak_probe": (_i32, [_p, _i32, _i32, _i32, _p]),
     "bnn_copy_probe": (_i32, [_p, _p, _sz, _p]),
 }
 
@@ -73,7 +82,7 @@ def lib() -> ctypes.CDLL:
                 f"{LIB_PATH} is missing: build it with `python paper_1911_04477_amd/build.py` "
                 "(there is no CPU fallback)")
         L = ctypes.CDLL(LIB_PATH)
-        for name, (res, args) in SIGNATURES.items():
+        for name, (res, args) in list(SIGNATURES.items()) + list(TESTING_SIGNATURES.items()):
             fn = getattr(L, name)
             fn.restype = res
             fn.argtypes = args
@@ -148,8 +157,10 @@ def bnn_im2col_packed(x: torch.Tensor, kH: int, kW: int, stride=(1, 1), pad=(0, 
     return cols
 
 
-def bnn_xnor_gemm(A: torch.Tensor, B: torch.Tensor, K: int, C: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """A [M, >=Kw], B [N, >=Kw] packed (int64-typed) -> int32 [M, N]."""
+def bnn_xnor_gemm(A: torch.Tensor, B: torch.Tensor, K: int, C: Optional[torch.Tensor] = None,
+                  cfg: Optional[int] = None) -> torch.Tensor:
+    """A [M, >=Kw], B [N, >=Kw] packed (int64-typed) -> int32 [M, N].
+    cfg (tests only): the same call through bnn_testing_xnor_gemm_epilogue on that tile configuration."""
     _dev(A, torch.int64, "A")
     _dev(B, torch.int64, "B")
     M, N = A.shape[0], B.shape[0]
@@ -158,8 +169,12 @@ def bnn_xnor_gemm(A: torch.Tensor, B: torch.Tensor, K: int, C: Optional[torch.Te
     _dev(C, torch.int32, "C")
     lda = A.stride(0) if M > 1 else max(A.shape[1], 1)
     ldb = B.stride(0) if N > 1 else max(B.shape[1], 1)
-    _check(lib().bnn_xnor_gemm(_ptr(A), lda, _ptr(B), ldb, _ptr(C), C.stride(0) if M > 1 else max(N, 1), M, N, K,
-                               _stream()), "bnn_xnor_gemm")
+    ldc = C.stride(0) if M > 1 else max(N, 1)
+    if cfg is None:
+        _check(lib().bnn_xnor_gemm(_ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc, M, N, K, _stream()), "bnn_xnor_gemm")
+    else:
+        _check(lib().bnn_testing_xnor_gemm_epilogue(_ptr(A), lda, _ptr(B), ldb, M, N, K, _ptr(C), ldc, None, 0, None,
+                                                    None, CH_NONE, cfg, _stream()), "bnn_testing_xnor_gemm_epilogue")
     return C
 
 
@@ -207,8 +222,8 @@ def bnn_control_conv2d_f32(x: torch.Tensor, w: torch.Tensor, stride=(1, 1), pad=
 
 
 def bnn_xnor_gemm_epilogue(A: torch.Tensor, B: torch.Tensor, K: int, scale: torch.Tensor, bias: torch.Tensor,
-                           axis: int, want_int: bool = False,
-                           out_y: Optional[torch.Tensor] = None) -> Tuple[Optional[torch.Tensor], torch.Tensor]:
+                           axis: int, want_int: bool = False, out_y: Optional[torch.Tensor] = None,
+                           cfg: Optional[int] = None) -> Tuple[Optional[torch.Tensor], torch.Tensor]:
     _dev(A, torch.int64, "A")
     _dev(B, torch.int64, "B")
     M, N = A.shape[0], B.shape[0]
@@ -219,8 +234,13 @@ def bnn_xnor_gemm_epilogue(A: torch.Tensor, B: torch.Tensor, K: int, scale: torc
     C = torch.empty((M, N), dtype=torch.int32, device=A.device) if want_int else None
     lda = A.stride(0) if M > 1 else max(A.shape[1], 1)
     ldb = B.stride(0) if N > 1 else max(B.shape[1], 1)
-    _check(lib().bnn_xnor_gemm_epilogue(_ptr(A), lda, _ptr(B), ldb, M, N, K, _ptr(C), max(N, 1), _ptr(Y), max(N, 1),
-                                        _ptr(scale), _ptr(bias), axis, _stream()), "bnn_xnor_gemm_epilogue")
+    if cfg is None:
+        _check(lib().bnn_xnor_gemm_epilogue(_ptr(A), lda, _ptr(B), ldb, M, N, K, _ptr(C), max(N, 1), _ptr(Y), max(N, 1),
+                                            _ptr(scale), _ptr(bias), axis, _stream()), "bnn_xnor_gemm_epilogue")
+    else:
+        _check(lib().bnn_testing_xnor_gemm_epilogue(_ptr(A), lda, _ptr(B), ldb, M, N, K, _ptr(C), max(N, 1), _ptr(Y),
+                                                    max(N, 1), _ptr(scale), _ptr(bias), axis, cfg, _stream()),
+               "bnn_testing_xnor_gemm_epilogue")
     return C, Y
 
 
@@ -232,8 +252,9 @@ def conv2d_workspace_bytes(x_shape, kH, kW, stride, pad) -> int:
 def bnn_conv2d(x: torch.Tensor, w_packed: torch.Tensor, D: int, kH: int, kW: int, stride=(1, 1), pad=(0, 0),
                scale: Optional[torch.Tensor] = None, bias: Optional[torch.Tensor] = None, want_int: bool = True,
                workspace: Optional[torch.Tensor] = None, out_i32: Optional[torch.Tensor] = None,
-               out_f32: Optional[torch.Tensor] = None):
-    """Returns (out_i32 or None, out_f32 or None), both NCHW."""
+               out_f32: Optional[torch.Tensor] = None, cfg: Optional[int] = None, lean: Optional[int] = None):
+    """Returns (out_i32 or None, out_f32 or None), both NCHW.
+    cfg / lean (tests only): the same call through bnn_testing_conv2d."""
     _dev(x, torch.float32, "x")
     _dev(w_packed, torch.int64, "w_packed")
     assert x.dim() == 4 and x.is_contiguous() and w_packed.is_contiguous()
@@ -246,16 +267,24 @@ def bnn_conv2d(x: torch.Tensor, w_packed: torch.Tensor, D: int, kH: int, kW: int
         out_i32 = torch.empty((N, D, OH, OW), dtype=torch.int32, device=x.device)
     if scale is not None and out_f32 is None:
         out_f32 = torch.empty((N, D, OH, OW), dtype=torch.float32, device=x.device)
-    _check(lib().bnn_conv2d(_ptr(x), _ptr(w_packed), N, C, H, W, D, kH, kW, stride[0], stride[1], pad[0], pad[1],
-                            _ptr(out_i32), _ptr(out_f32), _ptr(scale), _ptr(bias), _ptr(workspace),
-                            workspace.numel(), _stream()), "bnn_conv2d")
+    if cfg is None and lean is None:
+        _check(lib().bnn_conv2d(_ptr(x), _ptr(w_packed), N, C, H, W, D, kH, kW, stride[0], stride[1], pad[0], pad[1],
+                                _ptr(out_i32), _ptr(out_f32), _ptr(scale), _ptr(bias), _ptr(workspace),
+                                workspace.numel(), _stream()), "bnn_conv2d")
+    else:
+        _check(lib().bnn_testing_conv2d(_ptr(x), _ptr(w_packed), N, C, H, W, D, kH, kW, stride[0], stride[1], pad[0],
+                                        pad[1], _ptr(out_i32), _ptr(out_f32), _ptr(scale), _ptr(bias),
+                                        _ptr(workspace), workspace.numel(), -1 if cfg is None else cfg,
+                                        1 if lean is None else lean, _stream()), "bnn_testing_conv2d")
     return out_i32, out_f32
 
 
 def bnn_conv2d_packed(xp: torch.Tensor, w_packed: torch.Tensor, C: int, D: int, kH: int, kW: int, stride=(1, 1),
                       pad=(0, 0), pool: int = 0, scale: Optional[torch.Tensor] = None,
-                      bias: Optional[torch.Tensor] = None, out: str = "packed", out_buf: Optional[torch.Tensor] = None):
-    """xp: packed NHWC [N, H, W, Cw] (int64-typed).  out = "packed" | "i32" | "f32"."""
+                      bias: Optional[torch.Tensor] = None, out: str = "packed", out_buf: Optional[torch.Tensor] = None,
+                      cfg: Optional[int] = None, lean: Optional[int] = None):
+    """xp: packed NHWC [N, H, W, Cw] (int64-typed).  out = "packed" | "i32" | "f32".
+    cfg / lean (tests only): the same call through bnn_testing_conv2d_packed."""
     _dev(xp, torch.int64, "x_packed")
     _dev(w_packed, torch.int64, "w_packed")
     assert xp.dim() == 4 and xp.is_contiguous() and w_packed.is_contiguous()
@@ -272,9 +301,15 @@ def bnn_conv2d_packed(xp: torch.Tensor, w_packed: torch.Tensor, C: int, D: int, 
         of = out_buf if out_buf is not None else torch.empty((N, D, OH, OW), dtype=torch.float32, device=xp.device)
     else:
         raise ValueError(out)
-    _check(lib().bnn_conv2d_packed(_ptr(xp), _ptr(w_packed), N, C, H, W, D, kH, kW, stride[0], stride[1], pad[0],
-                                   pad[1], pool, _ptr(oi), _ptr(of), _ptr(op), _ptr(scale), _ptr(bias), _stream()),
-           "bnn_conv2d_packed")
+    if cfg is None and lean is None:
+        _check(lib().bnn_conv2d_packed(_ptr(xp), _ptr(w_packed), N, C, H, W, D, kH, kW, stride[0], stride[1], pad[0],
+                                       pad[1], pool, _ptr(oi), _ptr(of), _ptr(op), _ptr(scale), _ptr(bias), _stream()),
+               "bnn_conv2d_packed")
+    else:
+        _check(lib().bnn_testing_conv2d_packed(_ptr(xp), _ptr(w_packed), N, C, H, W, D, kH, kW, stride[0], stride[1],
+                                               pad[0], pad[1], pool, _ptr(oi), _ptr(of), _ptr(op), _ptr(scale),
+                                               _ptr(bias), -1 if cfg is None else cfg, 1 if lean is None else lean,
+                                               _stream()), "bnn_testing_conv2d_packed")
     return op if op is not None else (oi if oi is not None else of)
 
 
@@ -341,7 +376,7 @@ def bnn_fc_f32(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor] = 
     return out
 
 
-# ---- measurement helpers ---------------------------------------------------------
+# ---- measurement helpers (include/bnn_testing.h) -----------------------------------
 def prof_enable(on: bool) -> None:
     _check(lib().bnn_prof_enable(int(on)), "bnn_prof_enable")
 
@@ -361,10 +396,10 @@ def prof_records() -> List[Tuple[str, float]]:
     return out
 
 
-def bnn_valu_peak_probe(sink: torch.Tensor, blocks: int, iters: int) -> None:
+def bnn_valu_peak_probe(sink: torch.Tensor, blocks: int, iters: int, kind: int = 0) -> None:
     _dev(sink, torch.int32, "sink")
     assert sink.numel() >= blocks * 256
-    _check(lib().bnn_valu_peak_probe(_ptr(sink), blocks, iters, _stream()), "bnn_valu_peak_probe")
+    _check(lib().bnn_valu_peak_probe(_ptr(sink), blocks, iters, kind, _stream()), "bnn_valu_peak_probe")
 
 
 def bnn_copy_probe(src: torch.Tensor, dst: torch.Tensor) -> None:

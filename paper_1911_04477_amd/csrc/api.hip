@@ -2,6 +2,7 @@
 #include <vector>
 
 #include "common.h"
+#include "bnn_testing.h"
 
 extern "C" const char *bnn_status_str(bnn_status s) {
   switch (s) {

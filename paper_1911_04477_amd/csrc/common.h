@@ -101,16 +101,28 @@ struct GemmParams {
   int64_t img_stride;  // elements between images in C / Y
   int tilesM, tilesN;
   int prio_from;       // workgroups with id >= prio_from lower their wave priority as they advance through K
+  int n_cu;            // compute units of the device (host only: launch heuristics)
   ConvGeom g;          // implicit B only
   uint64_t *outp;      // packed-sign output [pixels, cw_out] (packed epilogue only)
   int cw_out;
 };
 
+// Per-call choice of the GEMM variant.  The entry points of bnn.h always pass the defaults (size
+// heuristic, table-driven gather where the geometry allows it); only the entry points of
+// bnn_testing.h pass anything else.  Every variant computes the same values.
+struct GemmTune {
+  int cfg = -1;   // tile configuration (numbering in bnn_testing.h); -1 = heuristic
+  int lean = 1;   // 0 = always the general implicit-GEMM gather
+};
+
+// Compute units of the current device (queried once per device, then cached).
+int device_cu_count();
+
 // Launch the exclusive-or / popcount GEMM described by p (tilesM / tilesN are filled in).
 // bmode 0: B is an explicit [N, ldb] matrix; 1: B is gathered from p.g (implicit GEMM; the
 // launcher switches to the lean gather, kernel mode 2, when the geometry allows it).
 // emode 0: int32 / fp32 store; 1: packed sign(fma(scale, acc, bias)) store, optional 2x2 pool.
-bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s);
+bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s, const GemmTune &tune = GemmTune());
 
 // Conv helpers (im2col.hip).  check_conv_geometry validates shapes and 32-bit limits;
 // run_im2col launches encode (+ gather) with already validated arguments.

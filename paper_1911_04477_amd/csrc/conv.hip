@@ -9,6 +9,7 @@
 //    the GEMM store), so a stack of binarized layers moves 1 bit per activation.
 //  * bnn_conv2d_f32_sign is the real-valued first layer producing that packed format.
 #include "common.h"
+#include "bnn_testing.h"
 
 namespace bnn {
 
@@ -34,7 +35,7 @@ static void fill_geom(ConvGeom &g, const uint64_t *act, int N, int C, int H, int
 static bnn_status conv_from_packed(const uint64_t *act, const uint64_t *w_packed, int N, int C, int H, int W, int D,
                                    int kH, int kW, int sH, int sW, int pH, int pW, int pool, int32_t *out_i32,
                                    float *out_f32, uint64_t *out_packed, const float *scale, const float *bias,
-                                   hipStream_t s) {
+                                   hipStream_t s, const GemmTune &tune) {
   const int64_t OH = bnn_conv_out_dim(H, kH, sH, pH), OW = bnn_conv_out_dim(W, kW, sW, pW);
   const int64_t Kw = bnn_conv_kwords(C, kH, kW);
   const int64_t cols = pool ? 4 * ((int64_t)N * (OH / 2) * (OW / 2)) : (int64_t)N * OH * OW;
@@ -62,7 +63,7 @@ static bnn_status conv_from_packed(const uint64_t *act, const uint64_t *w_packed
   fill_geom(p.g, act, N, C, H, W, kH, kW, sH, sW, pH, pW, pool);
   p.outp = out_packed;
   p.cw_out = (int)bnn_packed_words(D);
-  return run_gemm(p, 1, out_packed ? 1 : 0, s);
+  return run_gemm(p, 1, out_packed ? 1 : 0, s, tune);
 }
 
 static bnn_status conv_limits(int N, int C, int H, int W, int D, int kH, int kW, int sH, int sW, int pH, int pW) {
@@ -387,10 +388,10 @@ __global__ __launch_bounds__(256) void pack_fc_weight_nhwc_kernel(const float *_
 
 using namespace bnn;
 
-extern "C" bnn_status bnn_conv2d(const float *x, const uint64_t *w_packed, int N, int C, int H, int W, int D, int kH,
-                                 int kW, int sH, int sW, int pH, int pW, int32_t *out_i32, float *out_f32,
-                                 const float *scale, const float *bias, void *workspace, size_t workspace_bytes,
-                                 void *stream) {
+static bnn_status conv2d_impl(const float *x, const uint64_t *w_packed, int N, int C, int H, int W, int D, int kH,
+                              int kW, int sH, int sW, int pH, int pW, int32_t *out_i32, float *out_f32,
+                              const float *scale, const float *bias, void *workspace, size_t workspace_bytes,
+                              void *stream, const GemmTune &tune) {
   bnn_status st = check_conv_geometry(N, C, H, W, kH, kW, sH, sW, pH, pW);
   if (st != BNN_OK) return st;
   if (D < 0) return BNN_ERR_SHAPE;
@@ -412,18 +413,38 @@ extern "C" bnn_status bnn_conv2d(const float *x, const uint64_t *w_packed, int N
     st = launch_encode_nchw(x, N, C, H, W, OH, OW, sH, sW, img, s);
     if (st != BNN_OK) return st;
     return conv_from_packed(img, w_packed, N, C, OH, OW, D, 1, 1, 1, 1, 0, 0, 0, out_i32, out_f32, nullptr, scale,
-                            bias, s);
+                            bias, s, tune);
   }
   st = launch_encode_nchw(x, N, C, H, W, H, W, 1, 1, img, s);
   if (st != BNN_OK) return st;
   return conv_from_packed(img, w_packed, N, C, H, W, D, kH, kW, sH, sW, pH, pW, 0, out_i32, out_f32, nullptr, scale,
-                          bias, s);
+                          bias, s, tune);
 }
 
-extern "C" bnn_status bnn_conv2d_packed(const uint64_t *x_packed, const uint64_t *w_packed, int N, int C, int H, int W,
-                                        int D, int kH, int kW, int sH, int sW, int pH, int pW, int pool,
-                                        int32_t *out_i32, float *out_f32, uint64_t *out_packed, const float *scale,
-                                        const float *bias, void *stream) {
+extern "C" bnn_status bnn_conv2d(const float *x, const uint64_t *w_packed, int N, int C, int H, int W, int D, int kH,
+                                 int kW, int sH, int sW, int pH, int pW, int32_t *out_i32, float *out_f32,
+                                 const float *scale, const float *bias, void *workspace, size_t workspace_bytes,
+                                 void *stream) {
+  return conv2d_impl(x, w_packed, N, C, H, W, D, kH, kW, sH, sW, pH, pW, out_i32, out_f32, scale, bias, workspace,
+                     workspace_bytes, stream, GemmTune());
+}
+
+// Declared in bnn_testing.h.
+extern "C" bnn_status bnn_testing_conv2d(const float *x, const uint64_t *w_packed, int N, int C, int H, int W, int D,
+                                         int kH, int kW, int sH, int sW, int pH, int pW, int32_t *out_i32,
+                                         float *out_f32, const float *scale, const float *bias, void *workspace,
+                                         size_t workspace_bytes, int cfg, int lean, void *stream) {
+  GemmTune tune;
+  tune.cfg = cfg;
+  tune.lean = lean;
+  return conv2d_impl(x, w_packed, N, C, H, W, D, kH, kW, sH, sW, pH, pW, out_i32, out_f32, scale, bias, workspace,
+                     workspace_bytes, stream, tune);
+}
+
+static bnn_status conv2d_packed_impl(const uint64_t *x_packed, const uint64_t *w_packed, int N, int C, int H, int W,
+                                     int D, int kH, int kW, int sH, int sW, int pH, int pW, int pool,
+                                     int32_t *out_i32, float *out_f32, uint64_t *out_packed, const float *scale,
+                                     const float *bias, void *stream, const GemmTune &tune) {
   bnn_status st = check_conv_geometry(N, C, H, W, kH, kW, sH, sW, pH, pW);
   if (st != BNN_OK) return st;
   if (D < 0 || (pool != 0 && pool != 2)) return BNN_ERR_SHAPE;
@@ -440,7 +461,28 @@ extern "C" bnn_status bnn_conv2d_packed(const uint64_t *x_packed, const uint64_t
   st = conv_limits(N, C, H, W, D, kH, kW, sH, sW, pH, pW);
   if (st != BNN_OK) return st;
   return conv_from_packed(x_packed, w_packed, N, C, H, W, D, kH, kW, sH, sW, pH, pW, pool, out_i32, out_f32,
-                          out_packed, scale, bias, (hipStream_t)stream);
+                          out_packed, scale, bias, (hipStream_t)stream, tune);
+}
+
+extern "C" bnn_status bnn_conv2d_packed(const uint64_t *x_packed, const uint64_t *w_packed, int N, int C, int H, int W,
+                                        int D, int kH, int kW, int sH, int sW, int pH, int pW, int pool,
+                                        int32_t *out_i32, float *out_f32, uint64_t *out_packed, const float *scale,
+                                        const float *bias, void *stream) {
+  return conv2d_packed_impl(x_packed, w_packed, N, C, H, W, D, kH, kW, sH, sW, pH, pW, pool, out_i32, out_f32,
+                            out_packed, scale, bias, stream, GemmTune());
+}
+
+// Declared in bnn_testing.h.
+extern "C" bnn_status bnn_testing_conv2d_packed(const uint64_t *x_packed, const uint64_t *w_packed, int N, int C,
+                                                int H, int W, int D, int kH, int kW, int sH, int sW, int pH, int pW,
+                                                int pool, int32_t *out_i32, float *out_f32, uint64_t *out_packed,
+                                                const float *scale, const float *bias, int cfg, int lean,
+                                                void *stream) {
+  GemmTune tune;
+  tune.cfg = cfg;
+  tune.lean = lean;
+  return conv2d_packed_impl(x_packed, w_packed, N, C, H, W, D, kH, kW, sH, sW, pH, pW, pool, out_i32, out_f32,
+                            out_packed, scale, bias, stream, tune);
 }
 
 extern "C" bnn_status bnn_conv2d_f32_sign(const float *x, const float *w, int N, int C, int H, int W, int D, int kH,

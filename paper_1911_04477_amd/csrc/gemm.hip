@@ -828,8 +828,8 @@ __global__ __launch_bounds__(256) void xnor_gemm_direct_kernel(GemmParams p) {
 template <int TN, int WM, int WN, int MINW, int BMODE, int EMODE, int YIELD>
 static bnn_status launch_one(GemmParams &p, hipStream_t s, int kid) {
   using Cfg = GemmCfg<TN, WM, WN>;
-  // the last resident set: MINW waves per SIMD, 4 SIMDs, 256 compute units
-  const int64_t resident = (int64_t)(MINW * 4 / (Cfg::THREADS / 64)) * 256;
+  // the last resident set: MINW waves per SIMD, 4 SIMDs per compute unit
+  const int64_t resident = (int64_t)(MINW * 4 / (Cfg::THREADS / 64)) * p.n_cu;
   const int64_t nb = (int64_t)p.tilesM * p.tilesN;
   p.prio_from = (int)(nb > resident ? nb - resident : 0);
   ProfScope ps(kid, s);
@@ -846,9 +846,9 @@ static bnn_status launch_cfg(GemmParams &p, int bmode, int emode, hipStream_t s,
   const int64_t blocks = (int64_t)p.tilesM * p.tilesN;
   if (blocks > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   // The one-cycle yields after each xor/popcount pair pay off only when at least two waves
-  // share a SIMD; with fewer they cost issue slots.  256 CUs x 4 SIMDs.
+  // share a SIMD (4 per compute unit); with fewer they cost issue slots.
   const int64_t waves = blocks * (Cfg::THREADS / 64);
-  const bool yield = waves >= 2 * 1024;
+  const bool yield = waves >= 2 * 4 * (int64_t)p.n_cu;
   if constexpr ((TN == 4 || TN == 2) && (WM == 8 || WM == 4) && WN == 1) {
     if (emode == 1) {
       if (bmode == 0 || (p.g.pool && TN != 4)) return BNN_ERR_UNSUPPORTED;
@@ -865,8 +865,6 @@ static bnn_status launch_cfg(GemmParams &p, int bmode, int emode, hipStream_t s,
   return yield ? launch_one<TN, WM, WN, MINW, 0, 0, 1>(p, s, kid) : launch_one<TN, WM, WN, MINW, 0, 0, 0>(p, s, kid);
 }
 
-int g_force_cfg = -1;  // test / tuning hook: -1 = heuristic
-
 template <int TN>
 static bnn_status launch_direct(GemmParams &p, hipStream_t s, int ksplit = -1) {  // ksplit: -1 heuristic, 0 off, 1 on
   p.tilesM = (p.M + TM - 1) / TM;
@@ -874,10 +872,11 @@ static bnn_status launch_direct(GemmParams &p, hipStream_t s, int ksplit = -1) {
   const int64_t waves = (int64_t)p.tilesM * p.tilesN;
   if (waves > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   ProfScope ps(KID_XNOR_GEMM_SMALL, s);
+  const int64_t simds = 4 * (int64_t)p.n_cu;
   if constexpr (TN == 1) {
     // fewer tiles than SIMDs and at least four chunks per wave after the split: four waves per tile
-    if (ksplit > 0 || (ksplit < 0 && waves < 1024 && p.Kbits / (32 * KC) >= 16)) {
-      if (4 * waves >= 2 * 1024)
+    if (ksplit > 0 || (ksplit < 0 && waves < simds && p.Kbits / (32 * KC) >= 16)) {
+      if (4 * waves >= 2 * simds)
         hipLaunchKernelGGL((xnor_gemm_direct_kernel<1, 4, 1, 4>), dim3((unsigned)waves), dim3(256), 0, s, p);
       else
         hipLaunchKernelGGL((xnor_gemm_direct_kernel<1, 4, 0, 4>), dim3((unsigned)waves), dim3(256), 0, s, p);
@@ -885,18 +884,31 @@ static bnn_status launch_direct(GemmParams &p, hipStream_t s, int ksplit = -1) {
     }
   }
   const int64_t blocks = (waves + 3) / 4;
-  if (waves >= 2 * 1024)
+  if (waves >= 2 * simds)
     hipLaunchKernelGGL((xnor_gemm_direct_kernel<TN, 4, 1, 1>), dim3((unsigned)blocks), dim3(256), 0, s, p);
   else
     hipLaunchKernelGGL((xnor_gemm_direct_kernel<TN, 4, 0, 1>), dim3((unsigned)blocks), dim3(256), 0, s, p);
   return launch_status();
 }
 
-int g_lean_gather = 1;  // test hook: 0 keeps the general implicit-GEMM gather
+int device_cu_count() {
+  // one slot per device id; concurrent first calls write the same value
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    cached[dev] = n;
+  }
+  return cached[dev];
+}
 
-bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s) {
-  int cfg = g_force_cfg;
-  if (bmode == 1 && g_lean_gather) {
+bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s, const GemmTune &tune) {
+  int cfg = tune.cfg;
+  p.n_cu = device_cu_count();
+  const int64_t full = 2 * (int64_t)p.n_cu;  // tiles that give every compute unit two workgroups
+  if (bmode == 1 && tune.lean) {
     // lean gather: 16-byte pieces never straddle a tap (even Cw), one validity bit per tap in a
     // 32-bit mask, 32-bit byte offsets into the packed image
     const int64_t taps = (int64_t)p.g.kH * p.g.kW;
@@ -908,8 +920,8 @@ bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s) {
     // independent waves on 8 x 128 (or 8 x 64) tiles instead.
     const int64_t t32 = (int64_t)((p.M + 31) / 32) * ((p.N + 127) / 128);
     const int64_t w128 = (int64_t)((p.M + 7) / 8) * ((p.N + 127) / 128);
-    if (cfg == 8 || (cfg < 0 && t32 < 512 && w128 >= 2048)) return launch_direct<2>(p, s);
-    if (cfg == 7 || (cfg < 0 && t32 < 512)) return launch_direct<1>(p, s, cfg == 7 ? 0 : -1);
+    if (cfg == 8 || (cfg < 0 && t32 < full && w128 >= 4 * full)) return launch_direct<2>(p, s);
+    if (cfg == 7 || (cfg < 0 && t32 < full)) return launch_direct<1>(p, s, cfg == 7 ? 0 : -1);
   }
   if (bmode == 0 && emode == 0 && cfg == 9) return launch_direct<1>(p, s, 1);  // forced K split
   // a forced value this call cannot use (the one-wave kernels read an explicit B and store
@@ -922,7 +934,7 @@ bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s) {
     // 64 x 256 is the fastest tile when a compute unit gets more than two of them; with two or
     // fewer, 32 x 256 (four waves per workgroup, twice as many workgroups) is as fast or faster
     const int64_t t256 = (int64_t)((p.M + 63) / 64) * ((p.N + 255) / 256);
-    if (!ok) cfg = t256 <= 512 ? 1 : 3;
+    if (!ok) cfg = t256 <= full ? 1 : 3;
   }
   if (cfg < 0) {
     // Measured on MI355X: 64 x 256 (TN = 4, eight waves per workgroup, six per SIMD) is the
@@ -931,7 +943,7 @@ bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s) {
     const int64_t t256 = (int64_t)((p.M + 63) / 64) * ((p.N + 255) / 256);
     const int64_t t128 = (int64_t)((p.M + 63) / 64) * ((p.N + 127) / 128);
     const int64_t t32 = (int64_t)((p.M + 31) / 32) * ((p.N + 127) / 128);
-    cfg = (p.M >= 64 && t256 >= 512) ? 3 : (p.M >= 64 && t128 >= 512) ? 6 : (t32 >= 512 ? 4 : 2);
+    cfg = (p.M >= 64 && t256 >= full) ? 3 : (p.M >= 64 && t128 >= full) ? 6 : (t32 >= full ? 4 : 2);
   }
   switch (cfg) {
     case 1: return launch_cfg<4, 4, 1, 4>(p, bmode, emode, s, KID_XNOR_GEMM);        // 32 x 256
@@ -945,7 +957,7 @@ bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s) {
 
 static bnn_status gemm_common(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb, int64_t M, int64_t N,
                               int64_t K, int32_t *C, int64_t ldc, float *Y, int64_t ldy, const float *scale,
-                              const float *bias, bnn_ch_axis axis, void *stream) {
+                              const float *bias, bnn_ch_axis axis, void *stream, const GemmTune &tune = GemmTune()) {
   if (M < 0 || N < 0 || K <= 0) return BNN_ERR_SHAPE;
   const int64_t Kw = bnn_packed_words(K);
   if (lda < Kw || ldb < Kw) return BNN_ERR_STRIDE;
@@ -956,7 +968,8 @@ static bnn_status gemm_common(const uint64_t *A, int64_t lda, const uint64_t *B,
   if (Y && (!scale || !bias)) return BNN_ERR_NULL;
   if (Y && axis != BNN_CH_ROW && axis != BNN_CH_COL) return BNN_ERR_SHAPE;
   if (!aligned16(A) || !aligned16(B) || (C && !aligned16(C)) || (Y && !aligned16(Y))) return BNN_ERR_ALIGN;
-  if (M > 0x7fffffffLL || N > 0x7ffffff0LL || K > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+  // column indices are ints computed on N rounded up to the tile width (at most 256)
+  if (M > 0x7fffffffLL || N > 0x7fffffffLL - 256 || K > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   if (M * 8 * lda > 0xffffffffLL) return BNN_ERR_UNSUPPORTED;  // 32-bit byte offsets into A
   GemmParams p = {};
   p.A = reinterpret_cast<const uint32_t *>(A);
@@ -980,7 +993,7 @@ static bnn_status gemm_common(const uint64_t *A, int64_t lda, const uint64_t *B,
   p.OHW = 0x7fffffffu;
   p.divOHW = FastDiv(0x7fffffffu);
   p.img_stride = 0;
-  return run_gemm(p, 0, 0, (hipStream_t)stream);
+  return run_gemm(p, 0, 0, (hipStream_t)stream, tune);
 }
 
 }  // namespace bnn
@@ -999,6 +1012,12 @@ extern "C" bnn_status bnn_xnor_gemm_epilogue(const uint64_t *A, int64_t lda, con
   return gemm_common(A, lda, B, ldb, M, N, K, C, ldc, Y, ldy, scale, bias, axis, stream);
 }
 
-// Test and tuning switches, declared in bnn_testing.h.
-extern "C" void bnn_internal_force_gemm_cfg(int cfg) { g_force_cfg = cfg; }
-extern "C" void bnn_internal_lean_gather(int on) { g_lean_gather = on; }
+// Declared in bnn_testing.h: the same call with the tile configuration chosen by the caller.
+extern "C" bnn_status bnn_testing_xnor_gemm_epilogue(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb,
+                                                     int64_t M, int64_t N, int64_t K, int32_t *C, int64_t ldc,
+                                                     float *Y, int64_t ldy, const float *scale, const float *bias,
+                                                     bnn_ch_axis axis, int cfg, void *stream) {
+  GemmTune tune;
+  tune.cfg = cfg;
+  return gemm_common(A, lda, B, ldb, M, N, K, C, ldc, Y, ldy, scale, bias, axis, stream, tune);
+}

@@ -1,4 +1,4 @@
-// Glue kernels of the binarized VGG-small stack and the two measurement probes.
+// Glue kernels of the binarized VGG-small stack and the measurement yardsticks.
 // The paper's kernel covers the convolution only (section 4.4); these are the minimal
 // correctness-first pieces around it.  The fp32 layers use one thread per output and a
 // fixed sequential fma order so that their rounding is reproducible bit for bit (a
@@ -207,21 +207,16 @@ __global__ __launch_bounds__(256) void fc_f32_kernel(const float *__restrict__ x
   }
 }
 
-// 64 xor + popcount-accumulate pairs per round and nothing else in the loop body but
-// eight cheap updates of the xor operands (so nothing can be hoisted).
-// MODE 0: both xor operands in VGPRs, the compiler schedules the xors freely.
-// MODE 1: the GEMM's own instruction pattern: xor operand from an SGPR, each v_xor
-//         immediately followed by the v_bcnt that depends on it.
-// MODE 2: 128 v_xor only (VGPR operands).  MODE 3: 128 v_bcnt accumulates only.
-// MODE 4: dependent pairs, both operands in VGPRs.
-template <int MODE>
-__global__ __launch_bounds__(256) void valu_probe_kernel(int32_t *__restrict__ sink, int iters, uint32_t seed) {
+// Yardstick 0: 64 independent xor + popcount-accumulate pairs per round from registers and
+// nothing else in the loop body but eight cheap updates of the xor operands (so nothing can be
+// hoisted); the compiler schedules the xors freely.
+__global__ __launch_bounds__(256) void valu_probe_kernel(int32_t *__restrict__ sink, int iters) {
   const uint32_t tid = blockIdx.x * 256u + threadIdx.x;
   uint32_t a[8], b[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     b[j] = tid * 2654435761u + j * 40503u;
-    a[j] = 0x9e3779b9u * (j + 1) ^ (MODE == 1 ? seed : tid);
+    a[j] = 0x9e3779b9u * (j + 1) ^ tid;
   }
   int acc[64];
 #pragma unroll
@@ -229,34 +224,11 @@ __global__ __launch_bounds__(256) void valu_probe_kernel(int32_t *__restrict__ s
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int i = 0; i < 64; ++i) {
-      if (MODE == 0) {
-        const uint32_t x = a[i >> 3] ^ b[i & 7];
-        asm volatile("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc[i]) : "v"(x));
-      } else if (MODE == 1) {
-        uint32_t t;
-        asm volatile("v_xor_b32 %1, %2, %3\n\tv_bcnt_u32_b32 %0, %1, %0"
-                     : "+v"(acc[i]), "=&v"(t)
-                     : "s"(a[i >> 3]), "v"(b[i & 7]));
-      } else if (MODE == 2) {
-        asm volatile("v_xor_b32 %0, %1, %0\n\tv_xor_b32 %0, %2, %0" : "+v"(acc[i]) : "v"(a[i >> 3]), "v"(b[i & 7]));
-      } else if (MODE == 3) {
-        asm volatile("v_bcnt_u32_b32 %0, %1, %0\n\tv_bcnt_u32_b32 %0, %2, %0"
-                     : "+v"(acc[i])
-                     : "v"(a[i >> 3]), "v"(b[i & 7]));
-      } else {
-        uint32_t t;
-        asm volatile("v_xor_b32 %1, %2, %3\n\tv_bcnt_u32_b32 %0, %1, %0"
-                     : "+v"(acc[i]), "=&v"(t)
-                     : "v"(a[i >> 3]), "v"(b[i & 7]));
-      }
+      const uint32_t x = a[i >> 3] ^ b[i & 7];
+      asm volatile("v_bcnt_u32_b32 %0, %1, %0" : "+v"(acc[i]) : "v"(x));
     }
-    if (MODE == 1) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) a[j] = a[j] * 1664525u + 1013904223u;  // scalar ALU
-    } else {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) a[j] += b[j];
-    }
+    for (int j = 0; j < 8; ++j) a[j] += b[j];
   }
   int tot = 0;
 #pragma unroll
@@ -264,10 +236,10 @@ __global__ __launch_bounds__(256) void valu_probe_kernel(int32_t *__restrict__ s
   sink[tid] = tot;
 }
 
-// The GEMM's own per-row statements (8 rows x TN columns x 8 dwords) run from registers,
-// with no loads at all: the ceiling of that exact instruction sequence (V = 0 with the
-// one-cycle yield after each pair, V = 1 without).
-template <int TN, int V = 0>
+// Yardstick 1: the GEMM's own per-row statements (8 rows x TN columns x 8 dwords, xor operand
+// in a scalar register, one-cycle yield after each pair) run from registers with no loads at
+// all: the issue ceiling of exactly the instruction sequence the GEMM loop consists of.
+template <int TN>
 __global__ __launch_bounds__(256) void valu_rows_probe_kernel(int32_t *__restrict__ sink, int iters, uint32_t seed) {
   const uint32_t tid = blockIdx.x * 256u + threadIdx.x;
   typedef uint32_t u32x8 __attribute__((ext_vector_type(8)));
@@ -290,10 +262,8 @@ __global__ __launch_bounds__(256) void valu_rows_probe_kernel(int32_t *__restric
 #define BNN_BV(j, d) b[j][d]
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      if constexpr (TN == 4 && V == 0) BNN_GEMM_ROW_4(acc[i], a[i], BNN_BV, t0, t1);
-      else if constexpr (TN == 4) BNN_GEMM_ROW_4_NY(acc[i], a[i], BNN_BV, t0, t1);
-      else if constexpr (V == 0) BNN_GEMM_ROW_2(acc[i], a[i], BNN_BV, t0, t1);
-      else BNN_GEMM_ROW_2_NY(acc[i], a[i], BNN_BV, t0, t1);
+      if constexpr (TN == 4) BNN_GEMM_ROW_4(acc[i], a[i], BNN_BV, t0, t1);
+      else BNN_GEMM_ROW_2(acc[i], a[i], BNN_BV, t0, t1);
     }
 #undef BNN_BV
 #pragma unroll
@@ -307,39 +277,6 @@ __global__ __launch_bounds__(256) void valu_rows_probe_kernel(int32_t *__restric
   sink[tid] = tot;
 }
 
-// fp32 multiply-add throughput: 128 v_fmac_f32 per round on 16 independent accumulators.
-// SG = 1 takes the multiplier from an SGPR (as the real-valued first layer does), SG = 0
-// from a VGPR.
-template <int SG>
-__global__ __launch_bounds__(256) void fma_probe_kernel(int32_t *__restrict__ sink, int iters, uint32_t seed) {
-  const uint32_t tid = blockIdx.x * 256u + threadIdx.x;
-  float x[8], acc[16];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) x[j] = 1.0f + (float)((tid + j) & 7u) * 0.125f;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
-  float wv[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) wv[j] = 0.5f + (float)((SG ? seed : tid) + j) * 1e-3f;
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int r = 0; r < 8; ++r)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        if constexpr (SG) {
-          const float ws = __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(wv[(r + i) & 7])));
-          asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(acc[i]) : "s"(ws), "v"(x[r]));
-        } else {
-          asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(acc[i]) : "v"(wv[(r + i) & 7]), "v"(x[r]));
-        }
-      }
-  }
-  float tot = 0.0f;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) tot += acc[i];
-  sink[tid] = (int32_t)__float_as_uint(tot);
-}
-
 __global__ __launch_bounds__(256) void copy_probe_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst,
                                                          size_t n16) {
   size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
@@ -351,10 +288,6 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const uint4 *__restrict
 }  // namespace bnn
 
 using namespace bnn;
-
-static int g_probe_mode = 0;
-// Measurement switch, declared in bnn_testing.h.
-extern "C" void bnn_internal_probe_mode(int mode) { g_probe_mode = mode; }
 
 extern "C" bnn_status bnn_maxpool2x2(const int32_t *in, int N, int D, int H, int W, int32_t *out_i32, float *out_f32,
                                      const float *scale, const float *bias, void *stream) {
@@ -426,8 +359,8 @@ extern "C" bnn_status bnn_fc_f32(const float *x, const float *w, const float *bi
   return launch_status();
 }
 
-extern "C" bnn_status bnn_valu_peak_probe(int32_t *sink, int blocks, int iters, void *stream) {
-  if (blocks < 0 || iters < 0) return BNN_ERR_SHAPE;
+extern "C" bnn_status bnn_valu_peak_probe(int32_t *sink, int blocks, int iters, int kind, void *stream) {
+  if (blocks < 0 || iters < 0 || (kind != 0 && kind != 2 && kind != 4)) return BNN_ERR_SHAPE;
   if (blocks == 0) return BNN_OK;
   if (!sink) return BNN_ERR_NULL;
   if (!aligned16(sink)) return BNN_ERR_ALIGN;
@@ -435,20 +368,11 @@ extern "C" bnn_status bnn_valu_peak_probe(int32_t *sink, int blocks, int iters, 
   {
     ProfScope ps(KID_VALU_PROBE, s);
     const dim3 g((unsigned)blocks), b(256);
-    switch (g_probe_mode) {
-      case 1: hipLaunchKernelGGL(valu_probe_kernel<1>, g, b, 0, s, sink, iters, 1u); break;
-      case 2: hipLaunchKernelGGL(valu_probe_kernel<2>, g, b, 0, s, sink, iters, 1u); break;
-      case 3: hipLaunchKernelGGL(valu_probe_kernel<3>, g, b, 0, s, sink, iters, 1u); break;
-      case 4: hipLaunchKernelGGL(valu_probe_kernel<4>, g, b, 0, s, sink, iters, 1u); break;
-      // iters rounds of 8 x TN x 8 pairs: scale iters so that the lane-op count per launch matches
-      case 5: hipLaunchKernelGGL(valu_rows_probe_kernel<2>, g, b, 0, s, sink, iters / 2, 1u); break;
-      case 6: hipLaunchKernelGGL(valu_rows_probe_kernel<4>, g, b, 0, s, sink, iters / 4, 1u); break;
-      case 7: hipLaunchKernelGGL((valu_rows_probe_kernel<2, 1>), g, b, 0, s, sink, iters / 2, 1u); break;
-      case 8: hipLaunchKernelGGL((valu_rows_probe_kernel<4, 1>), g, b, 0, s, sink, iters / 4, 1u); break;
-      case 9: hipLaunchKernelGGL(fma_probe_kernel<0>, g, b, 0, s, sink, iters, 1u); break;
-      case 10: hipLaunchKernelGGL(fma_probe_kernel<1>, g, b, 0, s, sink, iters, 1u); break;
-      default: hipLaunchKernelGGL(valu_probe_kernel<0>, g, b, 0, s, sink, iters, 1u); break;
-    }
+    // a round of the row statements is 8 x TN x 8 pairs: iters is scaled so that every kind
+    // issues 2 * 64 * iters lane-operations per lane
+    if (kind == 2) hipLaunchKernelGGL(valu_rows_probe_kernel<2>, g, b, 0, s, sink, iters / 2, 1u);
+    else if (kind == 4) hipLaunchKernelGGL(valu_rows_probe_kernel<4>, g, b, 0, s, sink, iters / 4, 1u);
+    else hipLaunchKernelGGL(valu_probe_kernel, g, b, 0, s, sink, iters);
   }
   return launch_status();
 }

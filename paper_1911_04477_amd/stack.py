@@ -46,6 +46,7 @@ class VggStack:
                     b["y"] = torch.empty((batch, L.cout, L.hw, L.hw), dtype=torch.float32, device=self.dev)
             elif L.kind == "bfc":
                 b["xp"] = torch.empty((batch, B.packed_words(L.cin)), dtype=torch.int64, device=self.dev)
+                b["y"] = torch.empty((batch, L.cout), dtype=torch.float32, device=self.dev)
             elif L.kind == "fc_f32":
                 b["y"] = torch.empty((batch, L.cout), dtype=torch.float32, device=self.dev)
             self.buf.append(b)
@@ -67,7 +68,7 @@ class VggStack:
                                         want_int=False, workspace=self.ws, out_f32=b["y"])
             elif L.kind == "bfc":
                 xp = B.bnn_encode(h.view(self.batch, -1), b["xp"])
-                _, h = B.bnn_xnor_gemm_epilogue(xp, p["wp"], L.cin, p["scale"], p["bias"], B.CH_COL)
+                _, h = B.bnn_xnor_gemm_epilogue(xp, p["wp"], L.cin, p["scale"], p["bias"], B.CH_COL, out_y=b["y"])
             elif L.kind == "fc_f32":
                 h = B.bnn_fc_f32(h.view(self.batch, -1), p["w"], p["bias"], sign_input=True, out=b["y"])
             else:

@@ -38,10 +38,22 @@ def test_nothing_undeclared_is_exported(L):
     out = subprocess.check_output(["nm", "-D", "--defined-only", B.LIB_PATH], text=True)
     funcs = {ln.split()[2] for ln in out.splitlines() if len(ln.split()) == 3 and ln.split()[1] == "T"}
     hooks = _declared_functions("bnn_testing.h")
-    assert len(hooks) == 3
+    assert set(hooks) == set(B.TESTING_SIGNATURES), set(hooks) ^ set(B.TESTING_SIGNATURES)
     for n in hooks:
         assert hasattr(L, n), n
     assert funcs == set(_declared_functions()) | set(hooks), funcs ^ (set(_declared_functions()) | set(hooks))
+
+
+def test_no_exported_writable_state():
+    """What a call of bnn.h launches depends on its arguments only: the data symbols the library
+    exports are the compiler's kernel launch handles and its per-file id bytes, nothing of the
+    library's own, and none of the former process-wide switches exists."""
+    import subprocess
+    out = subprocess.check_output(["nm", "-D", "--defined-only", B.LIB_PATH], text=True)
+    data = [ln.split()[2] for ln in out.splitlines() if len(ln.split()) == 3 and ln.split()[1] not in ("T", "t")]
+    own = [n for n in data if not n.startswith("__hip_cuid_") and not re.match(r"_ZN3bnn\d+\w*_kernel", n)]
+    assert own == [], own
+    assert not any("internal" in ln or "force" in ln or "g_" in ln.split()[-1][:2] for ln in out.splitlines())
 
 
 def test_status_strings(L):
@@ -109,6 +121,8 @@ def test_gemm_errors(L):
     assert g(None, 4, A16, 4, A16, 8, 8, 8, 256, None) == NULL
     assert g(A16, 4, A16, 4, None, 8, 8, 8, 256, None) == NULL
     assert g(A16, 4, MIS, 4, A16, 8, 8, 8, 256, None) == ALIGN
+    # column indices are ints computed on N rounded up to the tile width
+    assert g(A16, 4, A16, 4, A16, 1 << 31, 8, (1 << 31) - 256, 256, None) == UNSUPPORTED
     e = L.bnn_xnor_gemm_epilogue
     assert e(A16, 4, A16, 4, 8, 8, 256, None, 8, None, 8, None, None, 0, None) == NULL  # no output at all
     assert e(A16, 4, A16, 4, 8, 8, 256, None, 8, A16, 8, None, A16, 1, None) == NULL  # Y without scale
@@ -196,8 +210,9 @@ def test_glue_errors(L):
     assert fc(A16, A16, None, 4, 0, 4, 0, A16, None) == SHAPE
     assert fc(A16, A16, None, 4, 8, 4, 0, None, None) == NULL
     assert fc(A16, MIS, None, 4, 8, 4, 0, A16, None) == ALIGN
-    assert L.bnn_valu_peak_probe(None, 4, 4, None) == NULL
-    assert L.bnn_valu_peak_probe(A16, -1, 4, None) == SHAPE
+    assert L.bnn_valu_peak_probe(None, 4, 4, 0, None) == NULL
+    assert L.bnn_valu_peak_probe(A16, -1, 4, 0, None) == SHAPE
+    assert L.bnn_valu_peak_probe(A16, 4, 4, 3, None) == SHAPE  # no such kind
     assert L.bnn_copy_probe(A16, A16, 24, None) == SHAPE
     assert L.bnn_copy_probe(A16, None, 32, None) == NULL
 

@@ -99,30 +99,24 @@ def _gemm_case(M, N, K, seed, cfg=None):
     A = inputs.inject_specials(rng.standard_normal((M, K)).astype(np.float32), seed, frac=0.002)
     Bm = inputs.inject_specials(rng.standard_normal((N, K)).astype(np.float32), seed + 1, frac=0.002)
     Ap, Bp = B.bnn_encode(dev(A)), B.bnn_encode(dev(Bm))
-    got = host(B.bnn_xnor_gemm(Ap, Bp, K))
+    got = host(B.bnn_xnor_gemm(Ap, Bp, K, cfg=cfg))
     assert np.array_equal(got, oracle.gemm_pm1(A, Bm))
 
 
-@pytest.mark.parametrize("K", [1, 31, 32, 33, 63, 64, 65, 200, 256, 257, 511, 512, 544, 1152, 2304 + 17])
+# K = 130 / 192 (three-word rows: dword-at-a-time tail), 400 / 704 (4n + 3 words: window chunk at an odd word)
+@pytest.mark.parametrize("K", [1, 31, 32, 33, 63, 64, 65, 130, 192, 200, 256, 257, 400, 511, 512, 544, 704, 1152,
+                               2304 + 17])
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 6, 7, 8, 9])
 def test_gemm_k_sweep_all_tile_configs(K, cfg):
     print(f"gemm K={K} cfg={cfg}", flush=True)
-    B.lib().bnn_internal_force_gemm_cfg(cfg)
-    try:
-        _gemm_case(37, 150, K, seed=K * 7 + cfg)
-    finally:
-        B.lib().bnn_internal_force_gemm_cfg(-1)
+    _gemm_case(37, 150, K, seed=K * 7 + cfg, cfg=cfg)
 
 
 @pytest.mark.parametrize("M,N", [(1, 1), (1, 700), (65, 513), (64, 512), (130, 1030), (257, 64), (33, 65)])
 @pytest.mark.parametrize("cfg", [1, 2, 3, 4, 6, 7, 8, 9])
 def test_gemm_ragged_tiles(M, N, cfg):
     print(f"gemm M={M} N={N} cfg={cfg}", flush=True)
-    B.lib().bnn_internal_force_gemm_cfg(cfg)
-    try:
-        _gemm_case(M, N, 300, seed=M * 1000 + N + cfg)
-    finally:
-        B.lib().bnn_internal_force_gemm_cfg(-1)
+    _gemm_case(M, N, 300, seed=M * 1000 + N + cfg, cfg=cfg)
 
 
 def test_gemm_table1_truth_table():
@@ -185,15 +179,11 @@ def test_gemm_fp32_epilogue_both_axes(M, N, K, cfg, axis):
     ref = oracle.gemm_pm1(A, Bm)
     yref = oracle.scale_bias(ref, sc, bi, axis)
     ax = B.CH_ROW if axis == "row" else B.CH_COL
-    B.lib().bnn_internal_force_gemm_cfg(cfg)
-    try:
-        C, Y = B.bnn_xnor_gemm_epilogue(Ap, Bp, K, dev(sc), dev(bi), ax, want_int=True)
-        assert np.array_equal(host(C), ref)
-        assert np.array_equal(host(Y), yref)
-        C, Y = B.bnn_xnor_gemm_epilogue(Ap, Bp, K, dev(sc), dev(bi), ax, want_int=False)
-        assert C is None and np.array_equal(host(Y), yref)
-    finally:
-        B.lib().bnn_internal_force_gemm_cfg(-1)
+    C, Y = B.bnn_xnor_gemm_epilogue(Ap, Bp, K, dev(sc), dev(bi), ax, want_int=True, cfg=cfg)
+    assert np.array_equal(host(C), ref)
+    assert np.array_equal(host(Y), yref)
+    C, Y = B.bnn_xnor_gemm_epilogue(Ap, Bp, K, dev(sc), dev(bi), ax, want_int=False, cfg=cfg)
+    assert C is None and np.array_equal(host(Y), yref)
 
 
 def test_gemm_deterministic_twice():
@@ -230,7 +220,9 @@ def test_cfg2_fc_layer_full_size():
     assert np.array_equal(got, yref)  # single-rounded fma on both sides: bit-exact
 
 
-def _conv_parity(shape, data, full=True, n_samples=200_000, with_epilogue=True):
+def _conv_parity(shape, data, with_epilogue=True):
+    """bnn_conv2d against the oracle's direct convolution on EVERY output: int32 bit-exact, and the
+    fp32 epilogue against oracle.scale_bias (1e-6 relative by contract, bit-exact by construction)."""
     x = inputs.inject_specials(data["x"], 7, frac=1e-4)
     w = data["w"]
     xd, wd = dev(x), dev(w)
@@ -241,42 +233,28 @@ def _conv_parity(shape, data, full=True, n_samples=200_000, with_epilogue=True):
                           bi if with_epilogue else None, want_int=True)
     got = host(oi)
     assert got.shape == (x.shape[0], shape.D, shape.OH, shape.OW)
-    if full:
-        ref = oracle.conv2d_pm1(x, w, st, pd)
-        assert np.array_equal(got, ref)
-        if with_epilogue:
-            yref = oracle.scale_bias(ref, data["scale"], data["bias"], "nchw")
-            assert_f32_close(host(of), yref)
-            assert np.array_equal(host(of), yref)
-    else:
-        rng = np.random.default_rng(99)
-        idx = np.unique(np.concatenate([rng.integers(0, got.size, n_samples), np.arange(0, 4096),
-                                        np.arange(got.size - 4096, got.size)]))
-        ref = oracle.conv2d_pm1_at(x, w, idx, st, pd)
-        assert np.array_equal(got.reshape(-1)[idx], ref)
-        # properties that hold for every output, at any size
-        K = shape.K
-        assert np.all((got - K) % 2 == 0) and np.all(np.abs(got) <= K)
-        if with_epilogue:
-            ch = (idx // (shape.OH * shape.OW)) % shape.D
-            yref = np.array([np.float32(np.float64(data["scale"][c]) * float(v) + np.float64(data["bias"][c]))
-                             for c, v in zip(ch[:2000], ref[:2000])], dtype=np.float32)
-            assert_f32_close(host(of).reshape(-1)[idx[:2000]], yref)
+    ref = oracle.conv2d_pm1(x, w, st, pd)
+    assert np.array_equal(got, ref)
+    if with_epilogue:
+        yref = oracle.scale_bias(ref, data["scale"], data["bias"], "nchw")
+        assert_f32_close(host(of), yref)
+        assert np.array_equal(host(of), yref)
 
 
 def test_cfg3_cifar_conv_full_size():
     print("cfg3", flush=True)
-    _conv_parity(inputs.CFG3, inputs.cfg3(), full=True)
+    _conv_parity(inputs.CFG3, inputs.cfg3())
 
 
-def test_cfg5a_imagenet_conv_sampled():
+def test_cfg5a_imagenet_conv_full_size():
+    """All 51.4 M int32 outputs and the fp32 epilogue of the ImageNet-shaped 3x3 convolution."""
     print("cfg5a", flush=True)
-    _conv_parity(inputs.CFG5A, inputs.cfg5a(), full=False)
+    _conv_parity(inputs.CFG5A, inputs.cfg5a())
 
 
 def test_cfg5b_ragged_k_pointwise_stride2_full_size():
     print("cfg5b", flush=True)
-    _conv_parity(inputs.CFG5B, inputs.cfg5b(), full=True)
+    _conv_parity(inputs.CFG5B, inputs.cfg5b())
 
 
 @pytest.mark.parametrize("case", CONV_CASES)
@@ -284,7 +262,7 @@ def test_conv2d_small_cases(case):
     print(f"conv case={case}", flush=True)
     N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
     shape = inputs.ConvShape(N, C, H, W, D, kH, kW, sH, sW, pH, pW)
-    _conv_parity(shape, inputs.conv_inputs(shape, seed=sum(case)), full=True)
+    _conv_parity(shape, inputs.conv_inputs(shape, seed=sum(case)))
 
 
 def test_conv2d_worked_examples():
@@ -355,17 +333,29 @@ def test_cfg4_stack_small_batch_every_layer(reading):
     assert np.array_equal(host(out), ref["out"])
 
 
-def test_cfg4_stack_full_batch_sampled_images():
-    """Batch 256 as benchmarked; the oracle runs the stack on a few images (images are
-    independent units) and those rows must match bit for bit."""
+@pytest.fixture(scope="module")
+def cfg4_b256():
+    """Config 4 at the benchmarked batch with the oracle's activations of every layer, all 256
+    images (computed once for the tests that use it)."""
+    d = inputs.cfg4(batch=256)
+    print("oracle: cfg4 stack, 256 images", flush=True)
+    ref = oracle.vgg_stack(d["x"], d["layers"], d["params"])
+    return d, ref
+
+
+def test_cfg4_stack_full_batch_every_layer_every_image(cfg4_b256):
+    """Batch 256 as benchmarked, through bnn_conv2d and the glue kernels: the activation of every
+    layer and the logits of all 256 images against the oracle, bit for bit."""
     print("cfg4 stack batch 256", flush=True)
     from paper_1911_04477_amd.stack import VggStack
-    d = inputs.cfg4(batch=256)
+    d, ref = cfg4_b256
     net = VggStack(d["layers"], d["params"], batch=256, device=DEV)
-    out = host(net.forward(dev(d["x"])))
-    pick = [0, 101, 255]
-    ref = oracle.vgg_stack(d["x"][pick], d["layers"], d["params"])
-    assert np.array_equal(out[pick], ref["out"])
+    out, acts = net.forward(dev(d["x"]), keep=True)
+    for i, (g, r) in enumerate(zip(acts, ref["acts"])):
+        assert np.array_equal(host(g).reshape(r.shape), r), f"layer {i} ({d['layers'][i].kind})"
+    out = host(out)
+    assert np.array_equal(out, ref["out"])
+    del acts
     out2 = host(net.forward(dev(d["x"])))
     assert np.array_equal(out, out2)
 
@@ -439,17 +429,17 @@ def test_conv2d_packed_forced_tiles(case, cfg):
     sc, bi = dev(d["scale"]), dev(d["bias"])
     st, pd = (sH, sW), (pH, pW)
     ref = oracle.conv2d_pm1(d["x"], d["w"], st, pd)
-    B.lib().bnn_internal_force_gemm_cfg(cfg)
-    try:
-        got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, scale=sc, bias=bi, out="packed"))
-        assert np.array_equal(got, oracle.pack_nhwc(oracle.scale_bias(ref, d["scale"], d["bias"], "nchw")))
-        if shape.OH % 2 == 0 and shape.OW % 2 == 0:
-            pref = oracle.scale_bias(oracle.maxpool2x2_i32(ref), d["scale"], d["bias"], "nchw")
-            got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, pool=2, scale=sc, bias=bi, out="packed"))
-            assert np.array_equal(got, oracle.pack_nhwc(pref))
-        assert np.array_equal(host(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, out="i32")), ref)
-    finally:
-        B.lib().bnn_internal_force_gemm_cfg(-1)
+    got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, scale=sc, bias=bi, out="packed", cfg=cfg))
+    assert np.array_equal(got, oracle.pack_nhwc(oracle.scale_bias(ref, d["scale"], d["bias"], "nchw")))
+    if shape.OH % 2 == 0 and shape.OW % 2 == 0:
+        pref = oracle.scale_bias(oracle.maxpool2x2_i32(ref), d["scale"], d["bias"], "nchw")
+        got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, pool=2, scale=sc, bias=bi, out="packed",
+                                         cfg=cfg))
+        assert np.array_equal(got, oracle.pack_nhwc(pref))
+    assert np.array_equal(host(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, out="i32", cfg=cfg)), ref)
+    # the same forced tile through bnn_conv2d (fp32 image in, int32 NCHW out)
+    oi, _ = B.bnn_conv2d(dev(d["x"]), wp, D, kH, kW, st, pd, want_int=True, cfg=cfg)
+    assert np.array_equal(host(oi), ref)
 
 
 @pytest.mark.parametrize("lean", [1, 0])
@@ -457,14 +447,10 @@ def test_conv2d_packed_forced_tiles(case, cfg):
 def test_conv2d_packed_all_output_kinds(case, lean):
     """lean = 0 forces the general implicit-GEMM gather also where the lean one applies."""
     print(f"conv2d_packed case={case} lean={lean}", flush=True)
-    B.lib().bnn_internal_lean_gather(lean)
-    try:
-        _conv2d_packed_all_output_kinds(case)
-    finally:
-        B.lib().bnn_internal_lean_gather(1)
+    _conv2d_packed_all_output_kinds(case, lean=lean)
 
 
-def _conv2d_packed_all_output_kinds(case):
+def _conv2d_packed_all_output_kinds(case, lean=None):
     N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
     shape = inputs.ConvShape(*case)
     d = inputs.conv_inputs(shape, seed=sum(case) + 2)
@@ -474,14 +460,14 @@ def _conv2d_packed_all_output_kinds(case):
     sc, bi = dev(d["scale"]), dev(d["bias"])
     st, pd = (sH, sW), (pH, pW)
     ref = oracle.conv2d_pm1(x, d["w"], st, pd)
-    assert np.array_equal(host(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, out="i32")), ref)
+    assert np.array_equal(host(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, out="i32", lean=lean)), ref)
     yref = oracle.scale_bias(ref, d["scale"], d["bias"], "nchw")
-    assert np.array_equal(host(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, scale=sc, bias=bi, out="f32")), yref)
-    got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, scale=sc, bias=bi, out="packed"))
+    assert np.array_equal(host(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, scale=sc, bias=bi, out="f32", lean=lean)), yref)
+    got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, scale=sc, bias=bi, out="packed", lean=lean))
     assert np.array_equal(got, oracle.pack_nhwc(yref))
     if shape.OH % 2 == 0 and shape.OW % 2 == 0:
         pref = oracle.scale_bias(oracle.maxpool2x2_i32(ref), d["scale"], d["bias"], "nchw")
-        got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, pool=2, scale=sc, bias=bi, out="packed"))
+        got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, pool=2, scale=sc, bias=bi, out="packed", lean=lean))
         assert np.array_equal(got, oracle.pack_nhwc(pref))
 
 
@@ -511,7 +497,7 @@ def test_conv_entry_points_on_random_geometries(case):
     N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
     shape = inputs.ConvShape(*case)
     d = inputs.conv_inputs(shape, seed=sum(case) + 11)
-    _conv_parity(shape, d, full=True)
+    _conv_parity(shape, d)
     _conv2d_packed_all_output_kinds(case)
     x = inputs.inject_specials(d["x"], 5, frac=0.01)
     cols = as_u64(B.bnn_im2col_packed(dev(x), kH, kW, (sH, sW), (pH, pW)))
@@ -599,19 +585,20 @@ def test_cfg4_fused_stack_graph_replays_match_oracle():
         _gemm_case(9, 70, 200, seed=rep)
 
 
-def test_cfg4_fused_stack_full_batch_sampled_images():
+def test_cfg4_fused_stack_full_batch_every_layer_every_image(cfg4_b256):
+    """The benchmark's default step (packed activations between layers, batch 256): every layer's
+    packed activation and the logits of all 256 images against the oracle."""
     print("cfg4 fused stack batch 256", flush=True)
-    from paper_1911_04477_amd.stack import VggStack, VggStackFused
-    d = inputs.cfg4(batch=256)
+    from paper_1911_04477_amd.stack import VggStackFused
+    d, ref = cfg4_b256
     net = VggStackFused(d["layers"], d["params"], batch=256, device=DEV)
-    xd = dev(d["x"])
-    out = host(net.forward(xd))
-    pick = [0, 57, 255]
-    ref = oracle.vgg_stack(d["x"][pick], d["layers"], d["params"])
-    assert np.array_equal(out[pick], ref["out"])
-    # and the whole batch against the unfused path (independent kernels, same arithmetic)
-    out_unfused = host(VggStack(d["layers"], d["params"], batch=256, device=DEV).forward(xd))
-    assert np.array_equal(out, out_unfused)
+    out, acts = net.forward(dev(d["x"]), keep=True)
+    for i, (L, g, r) in enumerate(zip(d["layers"], acts, ref["acts"])):
+        if L.kind in ("conv_f32", "bconv"):
+            assert np.array_equal(as_u64(g), oracle.pack_nhwc(r)), f"layer {i} ({L.kind})"
+        else:
+            assert np.array_equal(host(g), r), f"layer {i} ({L.kind})"
+    assert np.array_equal(host(out), ref["out"])
 
 
 # ---------------------------------------------------------------- MFMA ablation
@@ -684,11 +671,7 @@ def test_gemm_very_long_rows(cfg):
     Bm[1] = A[0]            # one identical pair: C = K
     Bm[2] = -A[1]           # one opposite pair: C = -K (no zeros in a normal sample)
     Ap, Bp = B.bnn_encode(dev(A)), B.bnn_encode(dev(Bm))
-    B.lib().bnn_internal_force_gemm_cfg(cfg)
-    try:
-        got = host(B.bnn_xnor_gemm(Ap, Bp, K))
-    finally:
-        B.lib().bnn_internal_force_gemm_cfg(-1)
+    got = host(B.bnn_xnor_gemm(Ap, Bp, K, cfg=None if cfg < 0 else cfg))
     assert got[0, 1] == K and got[1, 2] == -K
     # rows encoded by the oracle, not by the GPU
     assert np.array_equal(got, _popcount_rows(oracle.encode_rows(A), oracle.encode_rows(Bm), K))
