@@ -177,6 +177,26 @@ BNN_API size_t bnn_conv2d_workspace_bytes(int N, int C, int H, int W, int kH, in
                                   int pW);
 
 /*
+ * bnn_conv2d_noalloc -- bnn_conv2d for callers that cannot allocate device memory and have no
+ * workspace to hand over: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments (minus the workspace), same kernels, same results; the packed
+ * image goes to a fixed array of BNN_CONV2D_NOALLOC_MAX_BYTES in device memory that the library
+ * holds on every GPU it runs on until the process ends.  The call allocates and frees nothing.
+ *   - A problem whose bnn_conv2d_workspace_bytes() exceeds the limit returns BNN_ERR_WORKSPACE
+ *     (checked first, before any HIP call; nothing is launched).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ *     streams, two threads) race on it and must be serialised by the caller.  The array keeps the
+ *     previous call's contents; every word a call reads it has written first, so nothing needs
+ *     clearing.
+ *   - BNN_ERR_HIP if the array's device address cannot be obtained.
+ */
+#define BNN_CONV2D_NOALLOC_MAX_BYTES (8u << 20)
+BNN_API bnn_status bnn_conv2d_noalloc(const float *x, const uint64_t *w_packed, int N, int C, int H, int W,
+                                      int D, int kH, int kW, int sH, int sW, int pH, int pW, int32_t *out_i32,
+                                      float *out_f32, const float *scale, const float *bias, void *stream);
+BNN_API size_t bnn_conv2d_noalloc_max_bytes(void);
+
+/*
  * bnn_conv2d_packed -- the same forward graph with activations kept packed between
  * layers (1 bit per activation in memory): the input is a packed NHWC image, and with the
  * binarizing epilogue the output is the packed NHWC image the next layer consumes.

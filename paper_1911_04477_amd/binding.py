@@ -36,6 +36,8 @@ SIGNATURES = {
     "bnn_xnor_gemm_epilogue": (_i32, [_p, _i64, _p, _i64, _i64, _i64, _i64, _p, _i64, _p, _i64, _p, _p, _i32, _p]),
     "bnn_conv2d": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p, _p, _p, _p, _sz, _p]),
     "bnn_conv2d_workspace_bytes": (_sz, [_i32] * 10),
+    "bnn_conv2d_noalloc": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p, _p, _p, _p]),
+    "bnn_conv2d_noalloc_max_bytes": (_sz, []),
     "bnn_conv2d_packed": (_i32, [_p, _p] + [_i32] * 12 + [_p, _p, _p, _p, _p, _p]),
     "bnn_conv2d_f32_sign": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p, _p, _p]),
     "bnn_pack_fc_weight_nhwc": (_i32, [_p, _i64, _i32, _i32, _i32, _p, _p]),
@@ -277,6 +279,20 @@ def bnn_conv2d(x: torch.Tensor, w_packed: torch.Tensor, D: int, kH: int, kW: int
                                         _ptr(workspace), workspace.numel(), -1 if cfg is None else cfg,
                                         1 if lean is None else lean, _stream()), "bnn_testing_conv2d")
     return out_i32, out_f32
+
+
+def bnn_conv2d_noalloc(x: torch.Tensor, w_packed: torch.Tensor, D: int, kH: int, kW: int, stride, pad,
+                       out_i32: Optional[torch.Tensor], out_f32: Optional[torch.Tensor] = None,
+                       scale: Optional[torch.Tensor] = None, bias: Optional[torch.Tensor] = None) -> None:
+    """bnn_conv2d without a workspace argument; the caller passes every output buffer, so the call
+    allocates nothing on either side of the ABI."""
+    _dev(x, torch.float32, "x")
+    _dev(w_packed, torch.int64, "w_packed")
+    assert x.dim() == 4 and x.is_contiguous() and w_packed.is_contiguous()
+    N, C, H, W = x.shape
+    _check(lib().bnn_conv2d_noalloc(_ptr(x), _ptr(w_packed), N, C, H, W, D, kH, kW, stride[0], stride[1], pad[0],
+                                    pad[1], _ptr(out_i32), _ptr(out_f32), _ptr(scale), _ptr(bias), _stream()),
+           "bnn_conv2d_noalloc")
 
 
 def bnn_conv2d_packed(xp: torch.Tensor, w_packed: torch.Tensor, C: int, D: int, kH: int, kW: int, stride=(1, 1),

@@ -8,6 +8,8 @@
 //    the binarizing epilogue packed NHWC out (2x2 max-pool, affine map and sign fused into
 //    the GEMM store), so a stack of binarized layers moves 1 bit per activation.
 //  * bnn_conv2d_f32_sign is the real-valued first layer producing that packed format.
+#include <mutex>
+
 #include "common.h"
 #include "bnn_testing.h"
 
@@ -427,6 +429,57 @@ extern "C" bnn_status bnn_conv2d(const float *x, const uint64_t *w_packed, int N
                                  void *stream) {
   return conv2d_impl(x, w_packed, N, C, H, W, D, kH, kW, sH, sW, pH, pW, out_i32, out_f32, scale, bias, workspace,
                      workspace_bytes, stream, GemmTune());
+}
+
+// ---- bnn_conv2d for callers that cannot allocate ---------------------------------------------
+// The packed image goes to a fixed array in device memory instead of a caller workspace.  Every
+// GPU the library runs on holds its own copy of the array (at its own address) until the process
+// ends.  In host code the array's name is only a handle: its device address is looked up once per
+// device, with that device current, and from then on only that address is used.
+static __device__ __align__(256) unsigned char scratch[BNN_CONV2D_NOALLOC_MAX_BYTES];
+
+namespace {
+constexpr int NOALLOC_MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[NOALLOC_MAX_DEVICES] = {nullptr};
+
+// Device address of `scratch` on the current device, or nullptr on failure.
+void *scratch_address() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= NOALLOC_MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" size_t bnn_conv2d_noalloc_max_bytes(void) { return BNN_CONV2D_NOALLOC_MAX_BYTES; }
+
+extern "C" bnn_status bnn_conv2d_noalloc(const float *x, const uint64_t *w_packed, int N, int C, int H, int W, int D,
+                                         int kH, int kW, int sH, int sW, int pH, int pW, int32_t *out_i32,
+                                         float *out_f32, const float *scale, const float *bias, void *stream) {
+  // the size check comes first and needs no device: a request over the limit never reaches HIP
+  bnn_status st = check_conv_geometry(N, C, H, W, kH, kW, sH, sW, pH, pW);
+  if (st != BNN_OK) return st;
+  if (D < 0) return BNN_ERR_SHAPE;
+  if (N == 0 || D == 0) return BNN_OK;
+  const size_t need = bnn_conv2d_workspace_bytes(N, C, H, W, kH, kW, sH, sW, pH, pW);
+  if (need > BNN_CONV2D_NOALLOC_MAX_BYTES) return BNN_ERR_WORKSPACE;
+  if (!x || !w_packed || (!out_i32 && !out_f32)) return BNN_ERR_NULL;
+  if (out_f32 && (!scale || !bias)) return BNN_ERR_NULL;
+  if (!aligned16(x) || !aligned16(w_packed) || (out_i32 && !aligned16(out_i32)) || (out_f32 && !aligned16(out_f32)))
+    return BNN_ERR_ALIGN;
+  void *ptr = scratch_address();
+  if (!ptr) return BNN_ERR_HIP;
+  return conv2d_impl(x, w_packed, N, C, H, W, D, kH, kW, sH, sW, pH, pW, out_i32, out_f32, scale, bias, ptr,
+                     BNN_CONV2D_NOALLOC_MAX_BYTES, stream, GemmTune());
 }
 
 // Declared in bnn_testing.h.

@@ -165,6 +165,20 @@ def test_conv_and_im2col_errors(L):
     assert call(wb=need - 1) == WORKSPACE
 
 
+def test_noalloc_conv_errors_need_no_device(L):
+    """Size and argument checks of the entry point that allocates nothing run before any HIP call."""
+    na = L.bnn_conv2d_noalloc
+    assert L.bnn_conv2d_noalloc_max_bytes() == 8 << 20
+    geo = (2, 8, 6, 6, 4, 3, 3, 1, 1, 1, 1)
+    assert na(A16, A16, 128, 256, 56, 56, 256, 3, 3, 1, 1, 1, 1, A16, None, None, None, None) == WORKSPACE
+    assert na(A16, A16, 2, 8, 6, 6, 4, 7, 7, 1, 1, 0, 0, A16, None, None, None, None) == SHAPE
+    assert na(None, None, 0, 8, 6, 6, 4, 3, 3, 1, 1, 1, 1, None, None, None, None, None) == OK
+    assert na(None, A16, *geo, A16, None, None, None, None) == NULL
+    assert na(A16, A16, *geo, None, None, None, None, None) == NULL
+    assert na(A16, A16, *geo, None, A16, None, None, None) == NULL  # fp32 output without scale / bias
+    assert na(A16, MIS, *geo, A16, None, None, None, None) == ALIGN
+
+
 def test_packed_conv_errors(L):
     cp = L.bnn_conv2d_packed
     geo = (2, 128, 8, 8, 64, 3, 3, 1, 1, 1, 1)
