@@ -22,8 +22,14 @@ extern "C" {
  *    7  one wave per 8 x 64 tile, operand B read straight from memory (small problems)
  *    8  one wave per 8 x 128 tile, likewise
  *    9  as 7 with the reduction axis split over the four waves of a workgroup
+ *   13 .. 18  long rows, few outputs: one wave per (8 * T) x 64 tile slice, B kept in registers
+ *       across the T row groups, the reduction axis split over the S waves of a workgroup:
+ *       (T, S) = (4, 4), (4, 8), (2, 8), (2, 4), (4, 2), (2, 2)
+ *   10  the short-row kernel (rows of two or four words, four consecutive columns per lane,
+ *       16-byte stores), 8 rows per wave;   11, 12  the same with 16 / 32 rows per wave
  * A value that a call cannot use (the packed epilogue needs a 32- or 64-row tile with two or
- * four column groups; 7 to 9 exist for an explicit B with int32 / fp32 output only) selects the
+ * four column groups; 7 to 18 exist for an explicit B with int32 / fp32 output only, 10 to 12
+ * only where N, the leading dimensions and the pixels per image are multiples of 4) selects the
  * heuristic for that call.
  * `lean`: 1 = convolutions whose geometry allows it gather their patches with the table-driven
  * loader (what bnn.h's entry points do); 0 = always the general loader.

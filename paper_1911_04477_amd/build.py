@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbnn.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "encode.hip", "im2col.hip", "gemm.hip", "conv.hip", "glue.hip", "mfma.hip", "control.hip"]
+SOURCES = ["api.hip", "encode.hip", "im2col.hip", "gemm.hip", "gemm_lowk.hip", "conv.hip", "glue.hip", "mfma.hip", "control.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # Packed-FP32 VALU forms are disabled for all device code of this library.
@@ -34,7 +34,7 @@ def _compile(src: str) -> str:
 
 def build(verbose: bool = False) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(7, os.cpu_count() or 1)) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         objs = list(ex.map(_compile, SOURCES))
     tmp = LIB + ".tmp.%d" % os.getpid()
     subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", tmp])

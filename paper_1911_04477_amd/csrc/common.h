@@ -24,7 +24,8 @@ enum KernelId : int {
   KID_XNOR_GEMM_MFMA = 12,
   KID_CONTROL_CONV_F32 = 13,
   KID_XNOR_GEMM_MFMA_FP4 = 14,
-  KID_COUNT = 15
+  KID_XNOR_GEMM_LOWK = 15,
+  KID_COUNT = 16
 };
 
 // Timing hook: records an event pair around a launch when profiling is on.
@@ -123,6 +124,10 @@ int device_cu_count();
 // launcher switches to the lean gather, kernel mode 2, when the geometry allows it).
 // emode 0: int32 / fp32 store; 1: packed sign(fma(scale, acc, bias)) store, optional 2x2 pool.
 bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s, const GemmTune &tune = GemmTune());
+
+// Short-row GEMM (gemm_lowk.hip): rows of two or four words, explicit B, 16-byte stores.
+bool lowk_applicable(const GemmParams &p);
+bnn_status launch_lowk(GemmParams &p, int groups, hipStream_t s);
 
 // Conv helpers (im2col.hip).  check_conv_geometry validates shapes and 32-bit limits;
 // run_im2col launches encode (+ gather) with already validated arguments.

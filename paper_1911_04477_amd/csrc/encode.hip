@@ -155,6 +155,45 @@ __global__ __launch_bounds__(256) void encode_nchw_kernel(const float *__restric
   }
 }
 
+// The same encode for a column stride above 1 (the sampled pixels of a strided 1x1 / pad-0
+// convolution).  A wave's load then uses only every sW-th float of the sectors it touches, rows
+// between the sampled ones are skipped, and what bounds the kernel is how many independent
+// requests are in flight rather than bytes: a read-only kernel over the same addresses tops out
+// at 60 % of the streaming rate.  So every wave works alone on 64 pixels x ONE granule of 16
+// channels (16 loads in flight per lane), keeps its 16 sign bits per pixel and writes them
+// straight to its quarter of the pixel's word: no LDS, no barrier, four times as many waves.
+// The partial-word stores meet in the L2; the packed output is 1/32 of the input.  (Measured on
+// the 64 x 200 x 56 x 56 input with stride 2: 19.4 us against 24.1 us for the kernel above;
+// for stride 1 the kernel above is the faster one at every size tried.)
+constexpr int ENCS_GR = 16;
+__global__ __launch_bounds__(256) void encode_nchw_sampled_kernel(const float *__restrict__ x, int C, int H, int W,
+                                                                  int OHp, int OWp, int sH, int sW, FastDiv divOW,
+                                                                  FastDiv divOH, uint16_t *__restrict__ out,
+                                                                  uint32_t total_pix, int Cw) {
+  const uint32_t p = blockIdx.x * 256u + threadIdx.x;
+  const int g = blockIdx.y;  // granule: channels [16 g, 16 g + 16)
+  const uint32_t pc = p < total_pix ? p : total_pix - 1;  // lanes past the end re-read the last pixel
+  const uint32_t t = fdiv(pc, divOW);
+  const uint32_t ow = pc - t * OWp;
+  const uint32_t n = fdiv(t, divOH);
+  const uint32_t oh = t - n * OHp;
+  const size_t plane = (size_t)H * W;
+  const float *xp = x + (size_t)n * C * plane + (size_t)(oh * sH) * W + (size_t)ow * sW;
+  const int c0 = g * ENCS_GR;
+  const int left = C - c0;  // real channels in this granule; <= 0 for the padding granules of the last word
+  uint32_t acc = 0;
+  if (left > 0) {
+    float v[ENCS_GR];
+#pragma unroll
+    for (int j = 0; j < ENCS_GR; ++j)  // channels past C re-read the last channel and are masked out
+      v[j] = __builtin_nontemporal_load(xp + (size_t)(c0 + (j < left ? j : left - 1)) * plane);
+#pragma unroll
+    for (int j = 0; j < ENCS_GR; ++j) acc |= (uint32_t)sign_bit(v[j]) << j;
+    if (left < ENCS_GR) acc &= (1u << left) - 1u;
+  }
+  if (p < total_pix) out[(size_t)p * (4 * Cw) + g] = (uint16_t)acc;
+}
+
 }  // namespace bnn
 
 using namespace bnn;
@@ -219,6 +258,12 @@ bnn_status launch_encode_nchw(const float *x, int N, int C, int H, int W, int OH
   if ((span + 1) * (int64_t)C * H * W * 4 > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   FastDiv dOW((uint32_t)OWp), dOH((uint32_t)OHp);
   ProfScope ps(KID_ENCODE_NCHW, s);
+  if (sW > 1 && 4 * Cw <= 65535) {
+    const dim3 grid((unsigned)((total + 255) / 256), (unsigned)(4 * Cw));
+    hipLaunchKernelGGL(encode_nchw_sampled_kernel, grid, dim3(256), 0, s, x, C, H, W, OHp, OWp, sH, sW, dOW, dOH,
+                       reinterpret_cast<uint16_t *>(out), (uint32_t)total, Cw);
+    return launch_status();
+  }
   hipLaunchKernelGGL(encode_nchw_kernel, dim3(blocks), dim3(256), lds, s, x, C, H, W, OHp, OWp, sH, sW, dOW, dOH, out,
                      (uint32_t)total, Cw);
   return launch_status();

@@ -824,6 +824,146 @@ __global__ __launch_bounds__(256) void xnor_gemm_direct_kernel(GemmParams p) {
   store_tile<TN>(acc, m0, nbase);
 }
 
+// ---- few outputs, long rows: K split over the waves of a workgroup -----------------------------
+// A fully-connected layer (a few hundred rows of activations against thousands of filter rows)
+// has too few 8 x 64 tiles to give every SIMD its waves, and when every wave reads its own copy
+// of B straight from memory, as above, B crosses the L2 once per 8 rows of A: at M = 256 that is
+// 32 times the matrix, and that traffic, not the arithmetic, bounds the kernel.  Here a wave
+// keeps its chunk of B in registers while it walks 8 * TMG rows of A (8 at a time through the
+// scalar loads), so B is read once per 8 * TMG rows, and the parallelism lost to the taller tile
+// comes back from the reduction axis: the KS waves of a workgroup share one tile, each takes a
+// contiguous range of K chunks, and their partial counts (additive: section 3.2's sum over the
+// reduction axis) meet in LDS, where every wave adds up and stores its share of the rows.
+template <int TMG, int KS, int YIELD>
+__global__ __launch_bounds__(64 * KS) void xnor_gemm_splitk_kernel(GemmParams p) {
+  constexpr int DEPTH = 2;
+  __shared__ int sRed[KS * TMG * TM * 64];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const uint32_t tile = blockIdx.x;  // M fastest: consecutive workgroups share a B tile
+  const int mi = (int)(tile % (uint32_t)p.tilesM);
+  const int ni = (int)(tile / (uint32_t)p.tilesM);
+  const int m0 = mi * TM * TMG;
+  const int nbase = ni * 64 + lane;
+
+  const uint32_t arow_bytes = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)p.lda32 * 4u));
+  const uint32_t aoff_max = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(p.M - 1) * (uint32_t)p.lda32 * 4u));
+  const uint32_t aoff_tile = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)min(m0, p.M - 1) * (uint32_t)p.lda32 * 4u));
+  const uint32_t Abase_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)p.A);
+  const uint32_t Abase_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uintptr_t)p.A >> 32));
+  const uint64_t Abase0 = ((uint64_t)Abase_hi << 32) | (uint64_t)Abase_lo;
+  const cu32_ptr Ac = (cu32_ptr)(uintptr_t)p.A;
+
+  // this lane's row of B (clamped: columns past N recompute column N-1 and are not stored)
+  const uint64_t *brow = p.B + (int64_t)min(nbase, p.N - 1) * p.ldb;
+
+  int acc[TMG][TM][1];
+#pragma unroll
+  for (int g = 0; g < TMG; ++g)
+#pragma unroll
+    for (int i = 0; i < TM; ++i) acc[g][i][0] = 0;
+
+  const int nfull_all = p.Kbits / (32 * KC);
+  const int per = (nfull_all + KS - 1) / KS;
+  const int cb = min(wave * per, nfull_all);     // this wave's chunks: [cb, cb + nfull)
+  const int nfull = min(per, nfull_all - cb);
+  auto load_b = [&](u32x8 &b, int cl) {
+    const uint64_t *src = brow + 4 * (cb + cl);
+    if (p.b_vec16) {
+      b.lo = *reinterpret_cast<const u32x4 *>(src);
+      b.hi = *reinterpret_cast<const u32x4 *>(src + 2);
+    } else {
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(src + w);
+        b[2 * w] = v.x;
+        b[2 * w + 1] = v.y;
+      }
+    }
+  };
+  auto compute = [&](const u32x8 &bv, int cl) {
+    const uint64_t Abase = Abase0 + (uint64_t)(uint32_t)(cb + cl) * 32u;
+#pragma unroll
+    for (int g = 0; g < TMG; ++g) {
+      u32x8 a[TM];
+      uint32_t aoff_cur = aoff_tile + (uint32_t)(g * TM) * arow_bytes;
+      asm volatile("" : "+s"(aoff_cur));
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        asm volatile("s_load_dwordx8 %0, %1, %2" : "=s"(a[i]) : "s"(Abase), "s"(BNN_AOFF(i)));
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+s"(a[0]), "+s"(a[1]), "+s"(a[2]), "+s"(a[3]), "+s"(a[4]), "+s"(a[5]), "+s"(a[6]), "+s"(a[7]));
+      uint32_t t0, t1;
+#define BNN_BV(j, d) bv[d]
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        if constexpr (YIELD) BNN_GEMM_ROW_1(acc[g][i], a[i], BNN_BV, t0, t1);
+        else BNN_GEMM_ROW_1_NY(acc[g][i], a[i], BNN_BV, t0, t1);
+      }
+#undef BNN_BV
+    }
+  };
+
+  u32x8 bq[DEPTH];
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d)
+    if (d < nfull) load_b(bq[d], d);
+  int c = 0;
+  for (; c + DEPTH <= nfull; c += DEPTH) {
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) {
+      compute(bq[d], c + d);
+      if (c + d + DEPTH < nfull) load_b(bq[d], c + d + DEPTH);
+    }
+  }
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d)
+    if (c + d < nfull) compute(bq[d], c + d);
+
+  // bits past the last full chunk: one dword at a time, both operands masked (first wave only)
+  if (wave == 0) {
+    const int kd0 = nfull_all * KC;
+    const int tb32 = p.Kbits & 31;
+    const uint32_t *b32 = reinterpret_cast<const uint32_t *>(brow);
+#pragma unroll 1
+    for (int kd = kd0; kd < p.Kd; ++kd) {
+      const uint32_t mask = (kd == p.Kd - 1 && tb32) ? ((1u << tb32) - 1u) : 0xffffffffu;
+      const uint32_t b = b32[kd] & mask;
+#pragma unroll
+      for (int g = 0; g < TMG; ++g) {
+        uint32_t aoff_cur = aoff_tile + (uint32_t)(g * TM) * arow_bytes;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          const uint32_t a = Ac[(BNN_AOFF(i) >> 2) + kd] & mask;
+          acc[g][i][0] = popc_acc(a ^ b, acc[g][i][0]);
+        }
+      }
+    }
+  }
+
+  // partial counts -> LDS [slice][row][lane]; every wave then sums the row groups g = wave, wave + KS, ...
+#pragma unroll
+  for (int g = 0; g < TMG; ++g)
+#pragma unroll
+    for (int i = 0; i < TM; ++i) sRed[((wave * TMG + g) * TM + i) * 64 + lane] = acc[g][i][0];
+  __syncthreads();
+#pragma unroll
+  for (int g0 = 0; g0 < TMG; g0 += KS) {
+    const int g = g0 + wave;
+    if (g < TMG && m0 + g * TM < p.M) {  // wave-uniform
+      int tot[TM][1];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        int t = 0;
+#pragma unroll
+        for (int k = 0; k < KS; ++k) t += sRed[((k * TMG + g) * TM + i) * 64 + lane];
+        tot[i][0] = t;
+      }
+      store_tile<1>(tot, m0 + g * TM, nbase);
+    }
+  }
+}
+
 // ---- host side ----------------------------------------------------------------------
 template <int TN, int WM, int WN, int MINW, int BMODE, int EMODE, int YIELD>
 static bnn_status launch_one(GemmParams &p, hipStream_t s, int kid) {
@@ -904,10 +1044,58 @@ int device_cu_count() {
   return cached[dev];
 }
 
+template <int TMG, int KS>
+static bnn_status launch_splitk(GemmParams &p, hipStream_t s) {
+  p.tilesM = (p.M + TM * TMG - 1) / (TM * TMG);
+  p.tilesN = (p.N + 63) / 64;
+  const int64_t tiles = (int64_t)p.tilesM * p.tilesN;
+  if (tiles > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+  ProfScope ps(KID_XNOR_GEMM_SMALL, s);
+  if (tiles * KS >= 2 * 4 * (int64_t)p.n_cu)
+    hipLaunchKernelGGL((xnor_gemm_splitk_kernel<TMG, KS, 1>), dim3((unsigned)tiles), dim3(64 * KS), 0, s, p);
+  else
+    hipLaunchKernelGGL((xnor_gemm_splitk_kernel<TMG, KS, 0>), dim3((unsigned)tiles), dim3(64 * KS), 0, s, p);
+  return launch_status();
+}
+
+static bnn_status launch_splitk_by(GemmParams &p, int tmg, int ks, hipStream_t s) {
+  if (tmg == 4) {
+    if (ks == 8) return launch_splitk<4, 8>(p, s);
+    if (ks == 4) return launch_splitk<4, 4>(p, s);
+    if (ks == 2) return launch_splitk<4, 2>(p, s);
+  } else if (tmg == 2) {
+    if (ks == 8) return launch_splitk<2, 8>(p, s);
+    if (ks == 4) return launch_splitk<2, 4>(p, s);
+    if (ks == 2) return launch_splitk<2, 2>(p, s);
+  }
+  return BNN_ERR_UNSUPPORTED;
+}
+
 bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s, const GemmTune &tune) {
   int cfg = tune.cfg;
   p.n_cu = device_cu_count();
   const int64_t full = 2 * (int64_t)p.n_cu;  // tiles that give every compute unit two workgroups
+  if (bmode == 1 && emode == 0 && p.g.pool == 0 && p.g.kH == 1 && p.g.kW == 1 && p.g.sH == 1 && p.g.sW == 1 &&
+      p.g.pH == 0 && p.g.pW == 0) {
+    // a stride-1 pointwise convolution over a packed image has nothing to gather: its patch
+    // matrix is the packed image itself
+    bmode = 0;
+    p.B = p.g.act;
+    p.ldb = p.g.Cw;
+    p.b_vec16 = (p.g.Cw & 1) == 0 ? 1 : 0;
+  }
+  if (bmode == 0 && emode == 0 && (cfg < 0 || (cfg >= 10 && cfg <= 12)) && lowk_applicable(p) &&
+      ((int64_t)p.M + 31) / 32 <= 65535) {
+    // rows of two or four words: bound by the store, see gemm_lowk.hip.  As many rows per wave
+    // (32, 16 or 8) as still leave every compute unit a workgroup.
+    const int64_t ctiles = ((int64_t)p.N + 255) / 256;
+    const int groups = cfg == 12 ? 4 : cfg == 11 ? 2 : cfg == 10 ? 1
+                       : (ctiles * (((int64_t)p.M + 127) / 128) >= (int64_t)p.n_cu  ? 4
+                          : ctiles * (((int64_t)p.M + 63) / 64) >= (int64_t)p.n_cu ? 2
+                                                                                    : 1);
+    return launch_lowk(p, groups, s);
+  }
+  if (cfg >= 10 && cfg <= 12) cfg = -1;
   if (bmode == 1 && tune.lean) {
     // lean gather: 16-byte pieces never straddle a tap (even Cw), one validity bit per tap in a
     // 32-bit mask, 32-bit byte offsets into the packed image
@@ -920,10 +1108,30 @@ bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s, const Ge
     // independent waves on 8 x 128 (or 8 x 64) tiles instead.
     const int64_t t32 = (int64_t)((p.M + 31) / 32) * ((p.N + 127) / 128);
     const int64_t w128 = (int64_t)((p.M + 7) / 8) * ((p.N + 127) / 128);
+    const int nchunks = p.Kbits / (32 * KC);
+    if (cfg < 0 && t32 < full && nchunks >= 16 && ((int64_t)p.M + 32) * p.lda32 * 4 <= 0xffffffffLL) {
+      // long rows, few outputs: the tallest tile (32, 16 or 8 rows per wave, K split 8 / 8 / 4 ways over
+      // the waves of a workgroup) that still gives every SIMD two waves; if none does, the one
+      // with the most waves, the lower tile on a tie.  Measured: 256 x 4096 x 4096 12.8 -> 10.9 us,
+      // 256 x 1024 x 8192 8.4 -> 7.9 us per launch inside a replayed graph (an empty launch: 3.3 us).
+      const int64_t ct = ((int64_t)p.N + 63) / 64;
+      const int64_t w4 = (((int64_t)p.M + 31) / 32) * ct * 8, w2 = (((int64_t)p.M + 15) / 16) * ct * 8,
+                    w1 = (((int64_t)p.M + 7) / 8) * ct * 4;
+      const int64_t want = 2 * 4 * (int64_t)p.n_cu;
+      if (w4 >= want) return launch_splitk<4, 8>(p, s);
+      if (w2 >= want) return launch_splitk<2, 8>(p, s);
+      if (w1 < want && w2 > w1 && w2 >= w4) return launch_splitk<2, 8>(p, s);
+      if (w1 < want && w4 > w1 && w4 > w2) return launch_splitk<4, 8>(p, s);
+      return launch_direct<1>(p, s, 1);
+    }
     if (cfg == 8 || (cfg < 0 && t32 < full && w128 >= 4 * full)) return launch_direct<2>(p, s);
     if (cfg == 7 || (cfg < 0 && t32 < full)) return launch_direct<1>(p, s, cfg == 7 ? 0 : -1);
   }
   if (bmode == 0 && emode == 0 && cfg == 9) return launch_direct<1>(p, s, 1);  // forced K split
+  if (bmode == 0 && emode == 0 && cfg >= 13 && cfg <= 18) {
+    static const int tm[6] = {4, 4, 2, 2, 4, 2}, ks[6] = {4, 8, 8, 4, 2, 2};
+    return launch_splitk_by(p, tm[cfg - 13], ks[cfg - 13], s);
+  }
   // a forced value this call cannot use (the one-wave kernels read an explicit B and store
   // int32 / fp32; anything that is not a tile configuration) selects the heuristic
   if (cfg == 7 || cfg == 8 || cfg == 9 || cfg == 5 || cfg == 0 || cfg > 9) cfg = -1;

@@ -106,17 +106,75 @@ def _gemm_case(M, N, K, seed, cfg=None):
 # K = 130 / 192 (three-word rows: dword-at-a-time tail), 400 / 704 (4n + 3 words: window chunk at an odd word)
 @pytest.mark.parametrize("K", [1, 31, 32, 33, 63, 64, 65, 130, 192, 200, 256, 257, 400, 511, 512, 544, 704, 1152,
                                2304 + 17])
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 6, 7, 8, 9])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 6, 7, 8, 9, 13, 14, 15, 16, 17, 18])
 def test_gemm_k_sweep_all_tile_configs(K, cfg):
     print(f"gemm K={K} cfg={cfg}", flush=True)
     _gemm_case(37, 150, K, seed=K * 7 + cfg, cfg=cfg)
 
 
 @pytest.mark.parametrize("M,N", [(1, 1), (1, 700), (65, 513), (64, 512), (130, 1030), (257, 64), (33, 65)])
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 6, 7, 8, 9])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 6, 7, 8, 9, 13, 14, 15, 16, 17, 18])
 def test_gemm_ragged_tiles(M, N, cfg):
     print(f"gemm M={M} N={N} cfg={cfg}", flush=True)
     _gemm_case(M, N, 300, seed=M * 1000 + N + cfg, cfg=cfg)
+
+
+@pytest.mark.parametrize("cfg", [-1, 10, 11, 12])
+@pytest.mark.parametrize("M,N,K", [(37, 152, 200), (8, 4, 65), (64, 256, 256), (130, 1028, 193), (257, 516, 128),
+                                   (33, 260, 100), (70, 2052, 255), (5, 64, 129)])
+def test_gemm_short_rows_kernel(M, N, K, cfg):
+    """Rows of two or four words with N a multiple of 4: the store-bound kernel (four consecutive
+    columns per lane, 16-byte stores), 8 and 16 rows per wave, and whatever the heuristic picks;
+    int32 alone, and int32 + fp32 with the channel along either axis, on padded leading dimensions."""
+    print(f"gemm short rows M={M} N={N} K={K} cfg={cfg}", flush=True)
+    c = None if cfg < 0 else cfg
+    rng = np.random.default_rng(M * 31 + N + K)
+    A = inputs.inject_specials(rng.standard_normal((M, K)).astype(np.float32), 1, frac=0.01)
+    Bm = inputs.inject_specials(rng.standard_normal((N, K)).astype(np.float32), 2, frac=0.01)
+    Ap, Bp = as_u64(B.bnn_encode(dev(A))).copy(), as_u64(B.bnn_encode(dev(Bm))).copy()
+    tail = K % 64
+    if tail:  # garbage past K in both operands must not count
+        g = np.uint64((0xFFFFFFFFFFFFFFFF >> tail) << tail)
+        Ap[:, -1] |= g & np.uint64(0x5A5A5A5A5A5A5A5A)
+        Bp[:, -1] |= g & np.uint64(0xF0F0F0F00F0F0F0F)
+    Ad, Bd = dev(Ap.view(np.int64)), dev(Bp.view(np.int64))
+    ref = oracle.gemm_pm1(A, Bm)
+    Cbig = torch.full((M, N + 8), -7, dtype=torch.int32, device=DEV)
+    B.bnn_xnor_gemm(Ad, Bd, K, Cbig[:, :N], cfg=c)
+    out = host(Cbig)
+    assert np.array_equal(out[:, :N], ref) and np.all(out[:, N:] == -7)
+    for axis in ("row", "col"):
+        nch = M if axis == "row" else N
+        sc = ((rng.random(nch) + 0.5) * rng.choice([-1.0, 1.0], nch)).astype(np.float32)
+        bi = rng.standard_normal(nch).astype(np.float32)
+        Ci, Y = B.bnn_xnor_gemm_epilogue(Ad, Bd, K, dev(sc), dev(bi), B.CH_ROW if axis == "row" else B.CH_COL,
+                                         want_int=True, cfg=c)
+        assert np.array_equal(host(Ci), ref)
+        assert np.array_equal(host(Y), oracle.scale_bias(ref, sc, bi, axis))
+
+
+@pytest.mark.parametrize("cfg", [-1, 10, 11, 12, 3])
+@pytest.mark.parametrize("case", [(3, 200, 12, 12, 70, 1, 1, 2, 2, 0, 0),    # 36 pixels per image: short-row kernel
+                                  (2, 200, 10, 10, 17, 1, 1, 2, 2, 0, 0),    # 25 pixels per image: not a multiple of 4
+                                  (2, 128, 8, 8, 40, 1, 1, 1, 1, 0, 0),      # rows of two words, stride 1
+                                  (5, 256, 6, 4, 130, 1, 1, 1, 2, 0, 0),
+                                  (2, 100, 16, 16, 9, 1, 1, 2, 2, 0, 0),
+                                  (2, 250, 9, 12, 33, 1, 1, 3, 2, 0, 0)])    # odd H, stride (3, 2)
+def test_conv2d_pointwise_short_rows(case, cfg):
+    """1x1 / pad-0 convolutions with at most 256 channels: the encode samples the strided pixels
+    (8-byte loads on even rows with column stride 2) and the GEMM is the short-row kernel where the
+    image size allows it; int32 and fp32 outputs against the oracle."""
+    print(f"conv2d pointwise case={case} cfg={cfg}", flush=True)
+    N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
+    shape = inputs.ConvShape(*case)
+    d = inputs.conv_inputs(shape, seed=sum(case) + 21)
+    x = inputs.inject_specials(d["x"], 9, frac=0.01)
+    wp = B.bnn_pack_conv_weight(dev(d["w"]))
+    oi, of = B.bnn_conv2d(dev(x), wp, D, 1, 1, (sH, sW), (0, 0), dev(d["scale"]), dev(d["bias"]), want_int=True,
+                          cfg=None if cfg < 0 else cfg)
+    ref = oracle.conv2d_pm1(x, d["w"], (sH, sW), (0, 0))
+    assert np.array_equal(host(oi), ref)
+    assert np.array_equal(host(of), oracle.scale_bias(ref, d["scale"], d["bias"], "nchw"))
 
 
 def test_gemm_table1_truth_table():
@@ -163,8 +221,8 @@ def test_gemm_leading_dimensions():
 
 
 @pytest.mark.parametrize("axis", ["row", "col"])
-@pytest.mark.parametrize("cfg", [-1, 1, 2, 3, 4, 6, 7, 8, 9])
-@pytest.mark.parametrize("M,N,K", [(37, 150, 300), (130, 515, 1100), (8, 64, 64)])
+@pytest.mark.parametrize("cfg", [-1, 1, 2, 3, 4, 6, 7, 8, 9, 13, 14, 15, 16, 17, 18])
+@pytest.mark.parametrize("M,N,K", [(37, 150, 300), (130, 515, 1100), (8, 64, 64), (70, 200, 4096 + 77)])
 def test_gemm_fp32_epilogue_both_axes(M, N, K, cfg, axis):
     """y = fma(scale[ch], float(acc), bias[ch]) with the channel along rows or columns, with and
     without the int32 result beside it, on every tile configuration."""
@@ -660,7 +718,7 @@ def _popcount_rows(a_words, b_words, K):
     return (K - 2 * cnt).astype(np.int32)
 
 
-@pytest.mark.parametrize("cfg", [-1, 3, 7, 9])
+@pytest.mark.parametrize("cfg", [-1, 3, 7, 9, 14, 15])
 def test_gemm_very_long_rows(cfg):
     """K = 2^24 + 77 bits: 65536 full chunks and a ragged tail per row, accumulators in the millions."""
     print(f"gemm long K cfg={cfg}", flush=True)
