@@ -28,9 +28,13 @@ _lib = None
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        path = _build.LIB
-        if not os.path.exists(path):
-            _build.build()
+        if os.environ.get("ORACLE_SANITIZE") == "1":
+            # the ASan / UBSan build of the same source (the process must preload libasan)
+            path = _build.build_sanitized()
+        else:
+            path = _build.LIB
+            if not os.path.exists(path):
+                _build.build()
         L = ctypes.CDLL(path)
         i64, p, i32 = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
         L.oracle_sign.restype = ctypes.c_float

@@ -14,6 +14,21 @@ LIB = os.path.join(HERE, "liboracle.so")
 FLAGS = ["-O3", "-march=x86-64-v3", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC", "-Wall"]
 
 
+# Checker build (CPU only): AddressSanitizer + UndefinedBehaviorSanitizer, no OpenMP (its runtime's
+# own allocations drown the report), frame pointers for readable stacks.  Used as
+#   LD_PRELOAD=$(gcc -print-file-name=libasan.so) ORACLE_SANITIZE=1 python -m pytest tests/test_oracle_pins.py
+SAN_LIB = os.path.join(HERE, "liboracle_san.so")
+SAN_FLAGS = ["-O1", "-g", "-march=x86-64-v3", "-ffp-contract=off", "-fsanitize=address,undefined",
+             "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-shared", "-fPIC", "-Wall"]
+
+
+def build_sanitized() -> str:
+    tmp = SAN_LIB + ".tmp.%d" % os.getpid()
+    subprocess.check_call(["gcc", *SAN_FLAGS, SRC, "-o", tmp, "-lm"])
+    os.replace(tmp, SAN_LIB)
+    return SAN_LIB
+
+
 def build(force: bool = True) -> str:
     if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
         return LIB
@@ -24,4 +39,5 @@ def build(force: bool = True) -> str:
 
 
 if __name__ == "__main__":
-    print(build())
+    import sys
+    print(build_sanitized() if "--sanitize" in sys.argv[1:] else build())

@@ -15,7 +15,8 @@ from typing import List, Optional, Tuple
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libbnn.so")
+# BNN_SANITIZE=1 (host-only checks, see build.py): the build whose host code carries ASan / UBSan
+LIB_PATH = os.path.join(HERE, "libbnn_san.so" if os.environ.get("BNN_SANITIZE") == "1" else "libbnn.so")
 
 _i64, _i32, _p, _sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
 

@@ -26,6 +26,36 @@ FLAGS = [
 EXTRA_FLAGS = {"conv.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
+# Checker build of the HOST side (argument validation, dispatch, launch code) with AddressSanitizer
+# and UndefinedBehaviorSanitizer; device code is compiled as usual.  CPU-only use:
+#   python paper_1911_04477_amd/build.py --sanitize
+#   LD_PRELOAD="$(gcc -print-file-name=libasan.so) $(gcc -print-file-name=libubsan.so)" ASAN_OPTIONS=detect_leaks=0 \
+#       BNN_SANITIZE=1 python -m pytest tests/test_abi_host.py
+SAN_LIB = os.path.join(HERE, "libbnn_san.so")
+SAN_HOST_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+                  "-fno-omit-frame-pointer", "-g"]
+
+
+def build_sanitized() -> str:
+    out_dir = os.path.join(OBJ_DIR, "san")
+    os.makedirs(out_dir, exist_ok=True)
+    flags = [f if f != "-O3" else "-O1" for f in FLAGS]
+
+    def comp(src: str) -> str:
+        obj = os.path.join(out_dir, os.path.splitext(src)[0] + ".o")
+        subprocess.check_call([HIPCC, *flags, *SAN_HOST_FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src),
+                               "-o", obj])
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+        objs = list(ex.map(comp, SOURCES))
+    tmp = SAN_LIB + ".tmp.%d" % os.getpid()
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-Xarch_host", "-fsanitize=address",
+                           "-Xarch_host", "-fsanitize=undefined", *objs, "-o", tmp])
+    os.replace(tmp, SAN_LIB)
+    return SAN_LIB
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
     subprocess.check_call([HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj])
@@ -45,4 +75,8 @@ def build(verbose: bool = False) -> str:
 
 
 if __name__ == "__main__":
-    build(verbose=True)
+    import sys
+    if "--sanitize" in sys.argv[1:]:
+        print("built", build_sanitized())
+    else:
+        build(verbose=True)
