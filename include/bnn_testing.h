@@ -25,6 +25,9 @@ extern "C" {
  *   13 .. 18  long rows, few outputs: one wave per (8 * T) x 64 tile slice, B kept in registers
  *       across the T row groups, the reduction axis split over the S waves of a workgroup:
  *       (T, S) = (4, 4), (4, 8), (2, 8), (2, 4), (4, 2), (2, 2)
+ *   19, 20  the latency form of the implicit-GEMM convolution (32 x 64 tiles, one column per lane,
+ *       the reduction axis split over 4 / 2 slices inside a workgroup); needs an even number of
+ *       words per pixel
  *   10  the short-row kernel (rows of two or four words, four consecutive columns per lane,
  *       16-byte stores), 8 rows per wave;   11, 12  the same with 16 / 32 rows per wave
  * A value that a call cannot use (the packed epilogue needs a 32- or 64-row tile with two or

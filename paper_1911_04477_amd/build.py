@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbnn.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "encode.hip", "im2col.hip", "gemm.hip", "gemm_lowk.hip", "conv.hip", "glue.hip", "mfma.hip", "control.hip"]
+SOURCES = ["api.hip", "encode.hip", "im2col.hip", "gemm.hip", "gemm_lowk.hip", "gemm_latency.hip", "conv.hip", "glue.hip", "mfma.hip", "control.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # Packed-FP32 VALU forms are disabled for all device code of this library.

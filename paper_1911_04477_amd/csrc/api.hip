@@ -113,6 +113,7 @@ extern "C" const char *bnn_kernel_name(int kernel_id) {
     case bnn::KID_XNOR_GEMM: return "xnor_gemm";
     case bnn::KID_XNOR_GEMM_SMALL: return "xnor_gemm_small";
     case bnn::KID_XNOR_GEMM_LOWK: return "xnor_gemm_lowk";
+    case bnn::KID_XNOR_CONV_LATENCY: return "xnor_conv_latency";
     case bnn::KID_XNOR_GEMM_MFMA: return "xnor_gemm_mfma_i8";
     case bnn::KID_XNOR_GEMM_MFMA_FP4: return "xnor_gemm_mfma_fp4";
     case bnn::KID_CONTROL_CONV_F32: return "control_conv_f32";

@@ -25,7 +25,8 @@ enum KernelId : int {
   KID_CONTROL_CONV_F32 = 13,
   KID_XNOR_GEMM_MFMA_FP4 = 14,
   KID_XNOR_GEMM_LOWK = 15,
-  KID_COUNT = 16
+  KID_XNOR_CONV_LATENCY = 16,
+  KID_COUNT = 17
 };
 
 // Timing hook: records an event pair around a launch when profiling is on.
@@ -128,6 +129,11 @@ bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s, const Ge
 // Short-row GEMM (gemm_lowk.hip): rows of two or four words, explicit B, 16-byte stores.
 bool lowk_applicable(const GemmParams &p);
 bnn_status launch_lowk(GemmParams &p, int groups, hipStream_t s);
+
+// Latency form of the implicit-GEMM convolution (gemm_latency.hip): few output pixels, K split
+// over ks (2 or 4) slices inside a workgroup.  emode as for run_gemm.
+bool latency_applicable(const GemmParams &p);
+bnn_status launch_latency(GemmParams &p, int emode, int ks, hipStream_t s);
 
 // Conv helpers (im2col.hip).  check_conv_geometry validates shapes and 32-bit limits;
 // run_im2col launches encode (+ gather) with already validated arguments.

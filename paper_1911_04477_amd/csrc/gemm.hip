@@ -1096,6 +1096,17 @@ bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s, const Ge
     return launch_lowk(p, groups, s);
   }
   if (cfg >= 10 && cfg <= 12) cfg = -1;
+  if (bmode == 1 && (cfg == 19 || cfg == 20) && latency_applicable(p)) return launch_latency(p, emode, cfg == 19 ? 4 : 2, s);
+  if (cfg == 19 || cfg == 20) cfg = -1;
+  if (bmode == 1 && cfg < 0 && latency_applicable(p)) {
+    // Few output pixels (small batches, late layers): the latency form, see gemm_latency.hip.  Its
+    // workgroups fill a compute unit each, so it wins while there is at most one per compute unit
+    // (measured on the layers of the stack at batch 1 to 64: 1.5 to 2.2 times faster there, slower
+    // beyond); pooled layers, whose throughput tile is four columns wide, up to two per unit.
+    const int64_t lt = (((int64_t)p.M + 31) / 32) * (((int64_t)p.N + 63) / 64);
+    if (lt <= (int64_t)p.n_cu) return launch_latency(p, emode, 4, s);
+    if (p.g.pool && lt <= 2 * (int64_t)p.n_cu) return launch_latency(p, emode, 2, s);
+  }
   if (bmode == 1 && tune.lean) {
     // lean gather: 16-byte pieces never straddle a tap (even Cw), one validity bit per tap in a
     // 32-bit mask, 32-bit byte offsets into the packed image
@@ -1142,7 +1153,10 @@ bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s, const Ge
     // 64 x 256 is the fastest tile when a compute unit gets more than two of them; with two or
     // fewer, 32 x 256 (four waves per workgroup, twice as many workgroups) is as fast or faster
     const int64_t t256 = (int64_t)((p.M + 63) / 64) * ((p.N + 255) / 256);
-    if (!ok) cfg = t256 <= full ? 1 : 3;
+    // ... and without pooling 32 x 128 (again twice as many workgroups) while 32 x 256 would leave
+    // a compute unit two workgroups or fewer
+    const int64_t t32x256 = (int64_t)((p.M + 31) / 32) * ((p.N + 255) / 256);
+    if (!ok) cfg = (!p.g.pool && t32x256 <= full) ? 4 : (t256 <= full ? 1 : 3);
   }
   if (cfg < 0) {
     // Measured on MI355X: 64 x 256 (TN = 4, eight waves per workgroup, six per SIMD) is the

@@ -427,7 +427,7 @@ def test_prof_hook_records_kernels():
         Ap, Bp = B.bnn_encode(dev(d["A"])), B.bnn_encode(dev(d["B"]))
         B.bnn_xnor_gemm(Ap, Bp, 256)
         rec = B.prof_records()
-        assert [r[0] for r in rec] == ["encode_rows", "encode_rows", "xnor_gemm_small"]
+        assert [r[0] for r in rec] == ["encode_rows", "encode_rows", "xnor_gemm_lowk"]  # K = 256: the short-row kernel
         assert all(0.0 < r[1] < 50.0 for r in rec)
         B.prof_reset()
         assert B.prof_records() == []
@@ -472,7 +472,7 @@ PACKED_CASES = CONV_CASES + [
 ]
 
 
-@pytest.mark.parametrize("cfg", [1, 3, 4, 6, 9])
+@pytest.mark.parametrize("cfg", [1, 3, 4, 6, 9, 19, 20])
 @pytest.mark.parametrize("case", PACKED_CASES[-11:] + PACKED_CASES[1:4])
 def test_conv2d_packed_forced_tiles(case, cfg):
     """The binarizing epilogue on every tile shape it is written for (the pooled form only
