@@ -50,6 +50,9 @@ GEMM_TRAFFIC_BYTES = 3.81e6
 GEMM_TRAFFIC_BYTES_FETCH_SIZE_SCALED = 4.83e6
 
 
+NO_GRAPHS = False
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,6 +64,11 @@ def parse_args():
                     help="cfg4 only: activations packed between layers (fused) or fp32/int32 NCHW maps (unfused)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the per-kernel side measurements")
+    ap.add_argument("--no-graphs", action="store_true",
+                    help="time short kernels with eager launches instead of HIP-graph replays (for runs under rocprofv3 "
+                         "--pmc, whose counter collection does not survive a graph replay; the times are then not "
+                         "meaningful, the counters are)")
+    ap.add_argument("--no-sustained", action="store_true", help="skip the extra 200 + 1000 step run that a short --steps adds")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -83,6 +91,39 @@ def time_steps(fn, steps, warmup):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     return e0.elapsed_time(e1) / 1e3, wall
+
+
+def graph_time(fn, n=20, reps=20, warm=5):
+    """GPU seconds per call of fn: n calls captured into one HIP graph (the library neither allocates
+    nor synchronises, so the graph holds exactly the calls' kernels), replayed `reps` times between one
+    event pair.  Unlike an event pair around every launch (2-3 us on a 10 us kernel) and unlike eager
+    launches through the Python binding (the host cannot submit faster than one call per ~8 us), this
+    reads what the GPU needs for a short kernel sequence; an empty kernel reads ~3.3 us here."""
+    import torch
+    if NO_GRAPHS:
+        s, _ = time_steps(fn, 20, 5)
+        return s / 20
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(n):
+            fn()
+    for _ in range(warm):
+        g.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / 1e3 / (reps * n)
 
 
 def kernel_times(fn, reps):
@@ -202,9 +243,14 @@ def build_workload(name, args):
         sc, bi = up(d["scale"]), up(d["bias"])
         ap = torch.empty((s.M, B.packed_words(s.K)), dtype=torch.int64, device=dev)
 
+        yout = torch.empty((s.M, s.N), dtype=torch.float32, device=dev)
+
         def fn():
             B.bnn_encode(act, ap)
-            B.bnn_xnor_gemm_epilogue(ap, wp, s.K, sc, bi, B.CH_COL)
+            B.bnn_xnor_gemm_epilogue(ap, wp, s.K, sc, bi, B.CH_COL, out_y=yout)
+
+        def gemm_fn():
+            B.bnn_xnor_gemm_epilogue(ap, wp, s.K, sc, bi, B.CH_COL, out_y=yout)
 
         def oracle_sample(seconds):
             import oracle
@@ -217,8 +263,8 @@ def build_workload(name, args):
             oracle.scale_bias(oracle.gemm_pm1(d["act"][:n], d["wt"]), d["scale"], d["bias"], "col")
             return 2.0 * n * s.N * s.K, time.perf_counter() - t0, f"{n} of {s.M} activation rows"
 
-        return dict(fn=fn, bops=2.0 * s.M * s.N * s.K, gemm_shapes=[(s.M, s.N, s.K)], label="cfg2_binarized_fc_256x4096x4096",
-                    oracle=oracle_sample, extra={})
+        return dict(fn=fn, gemm_fn=gemm_fn, bops=2.0 * s.M * s.N * s.K, gemm_shapes=[(s.M, s.N, s.K)],
+                    label="cfg2_binarized_fc_256x4096x4096", oracle=oracle_sample, extra={})
 
     shape = {"cfg3": inputs.CFG3, "cfg5a": inputs.CFG5A, "cfg5b": inputs.CFG5B}[name]
     d = {"cfg3": inputs.cfg3, "cfg5a": inputs.cfg5a, "cfg5b": inputs.cfg5b}[name]()
@@ -230,6 +276,19 @@ def build_workload(name, args):
     def fn():
         B.bnn_conv2d(x, wp, shape.D, shape.kH, shape.kW, st, pd, want_int=True, workspace=ws, out_i32=out)
 
+    # the GEMM alone: the same convolution on the packed image the encode left in the workspace
+    fn()
+    if shape.kH == 1:
+        img = ws[:shape.P * B.packed_words(shape.C) * 8].view(torch.int64).view(shape.N, shape.OH, shape.OW, -1)
+        gst = (1, 1)
+    else:
+        img = ws[:shape.N * shape.H * shape.W * B.packed_words(shape.C) * 8].view(torch.int64).view(shape.N, shape.H,
+                                                                                                   shape.W, -1)
+        gst = st
+
+    def gemm_fn():
+        B.bnn_conv2d_packed(img, wp, shape.C, shape.D, shape.kH, shape.kW, gst, pd, out="i32", out_buf=out)
+
     def oracle_sample(seconds):
         import oracle
         t0 = time.perf_counter()
@@ -240,7 +299,7 @@ def build_workload(name, args):
         oracle.conv2d_pm1(d["x"][:n], d["w"], st, pd)
         return 2.0 * shape.bit_macs * n / shape.N, time.perf_counter() - t0, f"{n} of {shape.N} images"
 
-    return dict(fn=fn, bops=2.0 * shape.bit_macs, gemm_shapes=[(shape.D, shape.P, shape.K)],
+    return dict(fn=fn, gemm_fn=gemm_fn, bops=2.0 * shape.bit_macs, gemm_shapes=[(shape.D, shape.P, shape.K)],
                 label=f"{name}_binarized_conv_{shape.N}x{shape.C}x{shape.H}x{shape.W}_to_{shape.D}_k{shape.kH}s{shape.sH}p{shape.pH}",
                 oracle=oracle_sample, extra={})
 
@@ -279,26 +338,36 @@ def side_measurements():
     dt = t(lambda: B.bnn_encode(w, dst[:4096]))
     res["encode_cfg2_weights_GBs"] = round((w.numel() * 4 + 4096 * 64 * 8) / dt / 1e9, 1)
     del src, dst, a
-    # input encode + packed im2col at the conv configurations
+    # input encode + packed im2col at the conv configurations: the whole bnn_im2col_packed call (one or
+    # two kernels) by graph replay, its kernels by the event hook, and a plain copy moving the same
+    # number of bytes beside it
     for name, shape in (("cfg3", inputs.CFG3), ("cfg5a", inputs.CFG5A), ("cfg5b", inputs.CFG5B)):
         x = torch.randn((shape.N, shape.C, shape.H, shape.W), device=dev)
-        geo = (shape.kH, shape.kW, (shape.sH, shape.sW), (shape.pH, shape.pW))
-        fn = lambda: B.bnn_im2col_packed(x, *geo)
-        kt = kt_warm(fn)
+        st, pd = (shape.sH, shape.sW), (shape.pH, shape.pW)
         Cw = B.packed_words(shape.C)
         Kw = B.conv_kwords(shape.C, shape.kH, shape.kW)
+        cols = torch.empty((shape.P, Kw), dtype=torch.int64, device=dev)
+        wsb = torch.empty(max(16, B.im2col_workspace_bytes(x.shape, shape.kH, shape.kW, st, pd)), dtype=torch.uint8,
+                          device=dev)
+        fn = lambda: B.bnn_im2col_packed(x, shape.kH, shape.kW, st, pd, cols=cols, workspace=wsb)
+        tot = graph_time(fn)
+        kt = kt_warm(fn)
+        # algorithmic bytes: the fp32 values the convolution uses + the patch matrix written
+        used = x.numel() * 4 * (0.25 if shape.sH == 2 else 1.0)
+        byts = used + shape.P * Kw * 8
+        res[f"{name}_im2col_total_GBs"] = round(byts / tot / 1e9, 1)
+        res[f"{name}_im2col_total_us"] = round(tot * 1e6, 2)
+        half = int(byts // 32) * 16
+        ca = torch.empty(half, dtype=torch.uint8, device=dev)
+        cb = torch.empty(half, dtype=torch.uint8, device=dev)
+        res[f"{name}_copy_same_bytes_us"] = round(graph_time(lambda: B.bnn_copy_probe(ca, cb)) * 1e6, 2)
         if "encode_nchw" in kt:
-            if shape.kH == 1:
-                byts = shape.P * shape.C * 4 + shape.P * Cw * 8
-            else:
-                byts = x.numel() * 4 + shape.N * shape.H * shape.W * Cw * 8
-            res[f"{name}_encode_nchw_GBs"] = round(byts / kt["encode_nchw"] / 1e9, 1)
+            eb = (shape.P * shape.C * 4 + shape.P * Cw * 8) if shape.kH == 1 else (x.numel() * 4 + shape.N * shape.H * shape.W * Cw * 8)
+            res[f"{name}_encode_nchw_GBs_event_hook"] = round(eb / kt["encode_nchw"] / 1e9, 1)
         if "im2col_gather" in kt:
-            byts = shape.P * Kw * 8 + shape.N * shape.H * shape.W * Cw * 8
-            res[f"{name}_im2col_gather_GBs"] = round(byts / kt["im2col_gather"] / 1e9, 1)
-        tot = sum(kt.values())
-        res[f"{name}_im2col_total_GBs"] = round((x.numel() * 4 * (0.25 if shape.sH == 2 else 1.0) + shape.P * Kw * 8) / tot / 1e9, 1)
-        del x
+            gb = shape.P * Kw * 8 + shape.N * shape.H * shape.W * Cw * 8
+            res[f"{name}_im2col_gather_GBs_event_hook"] = round(gb / kt["im2col_gather"] / 1e9, 1)
+        del x, cols, wsb, ca, cb
     # the same two kernels on an input several times larger than the 256 MB last-level cache:
     # encode 822 MB in / 26 MB out; gather 26 MB in / 231 MB out
     x = torch.randn((256, 256, 56, 56), device=dev)
@@ -429,24 +498,49 @@ def unfused_stack(args):
 
 
 def other_configs(args):
+    """The other configurations: whole call and GEMM alone, GPU time per call from graph replays (these
+    kernels last 10-200 us; see graph_time), and the per-kernel split from the library's event hook."""
     out = {}
     for name in ("cfg2", "cfg3", "cfg5a", "cfg5b"):
         wl = build_workload(name, args)
-        s, _ = time_steps(wl["fn"], 300, 100)
-        per = s / 300
+        per = graph_time(wl["fn"])
+        g = graph_time(wl["gemm_fn"])
         kt, _ = kernel_times(wl["fn"], 10)
-        g = sum(v for k, v in kt.items() if k.startswith("xnor_gemm"))
         lane = sum(gemm_laneops(*sh) for sh in wl["gemm_shapes"])
         out[name] = {"TBOPS_end_to_end": round(wl["bops"] / per / 1e12, 2), "ms": round(per * 1e3, 4),
-                     "TBOPS_gemm_only": round(wl["bops"] / g / 1e12, 2),
+                     "gemm_ms": round(g * 1e3, 4), "TBOPS_gemm_only": round(wl["bops"] / g / 1e12, 2),
                      "gemm_frac_valu_peak": round(lane / g / 1e12 / VALU_PEAK_TLANEOPS, 4),
-                     "kernels_ms": {k: round(v * 1e3, 4) for k, v in kt.items()}}
+                     "kernels_ms_event_hook": {k: round(v * 1e3, 4) for k, v in kt.items()}}
+        if name == "cfg5b":
+            sh = inputs_shape("cfg5b")
+            out[name]["gemm_store_GBs"] = round(sh.D * sh.P * 4 / g / 1e9, 1)
         del wl
     return out
 
 
+def inputs_shape(name):
+    from paper_1911_04477_amd import inputs
+    return {"cfg3": inputs.CFG3, "cfg5a": inputs.CFG5A, "cfg5b": inputs.CFG5B}[name]
+
+
+def reading_b_step(args):
+    """Config 4 under its second reading (six binarized convolutions after the real-valued one)."""
+    import torch
+    from paper_1911_04477_amd import inputs
+    from paper_1911_04477_amd.stack import VggStackFused
+    d = inputs.cfg4(batch=256, reading="B")
+    net = VggStackFused(d["layers"], d["params"], batch=256, device="cuda:0")
+    x = torch.from_numpy(np.ascontiguousarray(d["x"])).to("cuda:0")
+    s, _ = time_steps(lambda: net.forward(x), 500, 200)
+    per = s / 500
+    bops = 2.0 * inputs.stack_bit_macs(d["layers"], 256)
+    return {"ms_per_step": round(per * 1e3, 4), "TBOPS": round(bops / per / 1e12, 2), "GBOP_per_step": round(bops / 1e9, 1)}
+
+
 def main():
+    global NO_GRAPHS
     args = parse_args()
+    NO_GRAPHS = args.no_graphs
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
@@ -553,12 +647,20 @@ def main():
         s2 = e0.elapsed_time(e1) / 1e3
         line["two_half_batches_on_two_streams"] = {"ms_per_step": round(s2 / args.steps * 1e3, 4),
                                                    "TBOPS": round(wl["bops"] / (s2 / args.steps) / 1e12, 3)}
+    if (args.steps < 200 or args.warmup < 100) and not args.no_sustained:
+        # the same step after the clocks have settled (a few hundred steps of continuous work)
+        s3, _ = time_steps(wl["fn"], 1000, 200)
+        line["sustained"] = {"steps": 1000, "warmup": 200, "ms_per_step": round(s3 / 1000 * 1e3, 4),
+                             "value": round(wl["bops"] / (s3 / 1000) / 1e12, 3)}
     if not args.no_extras:
         line["streaming"] = side_measurements()
         line["hbm_peak_GBs"] = HBM_PEAK_GBS
         if args.workload == "cfg4" and args.stack == "fused":
             line["unfused_stack"] = unfused_stack(args)
-            line["small_batch_latency"] = small_batch_latency(args)
+            if args.reading == "A":
+                line["reading_B_fused_stack"] = reading_b_step(args)
+            if not args.no_graphs:
+                line["small_batch_latency"] = small_batch_latency(args)
         line["other_configs"] = other_configs(args)
         line["mfma_ablation"] = mfma_ablation()
         line["control_group"] = control_group()

@@ -147,16 +147,27 @@ def bnn_pack_conv_weight(w: torch.Tensor) -> torch.Tensor:
     return out
 
 
-def bnn_im2col_packed(x: torch.Tensor, kH: int, kW: int, stride=(1, 1), pad=(0, 0)) -> torch.Tensor:
+def im2col_workspace_bytes(x_shape, kH, kW, stride, pad) -> int:
+    N, C, H, W = x_shape
+    return int(lib().bnn_im2col_workspace_bytes(N, C, H, W, kH, kW, stride[0], stride[1], pad[0], pad[1]))
+
+
+def bnn_im2col_packed(x: torch.Tensor, kH: int, kW: int, stride=(1, 1), pad=(0, 0),
+                      cols: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     _dev(x, torch.float32, "x")
     assert x.dim() == 4 and x.is_contiguous()
     N, C, H, W = x.shape
     geo = (N, C, H, W, kH, kW, stride[0], stride[1], pad[0], pad[1])
     OH, OW = conv_out_dim(H, kH, stride[0], pad[0]), conv_out_dim(W, kW, stride[1], pad[1])
-    cols = torch.empty((N * OH * OW, conv_kwords(C, kH, kW)), dtype=torch.int64, device=x.device)
+    if cols is None:
+        cols = torch.empty((N * OH * OW, conv_kwords(C, kH, kW)), dtype=torch.int64, device=x.device)
+    _dev(cols, torch.int64, "cols")
+    assert cols.is_contiguous() and cols.numel() == N * OH * OW * conv_kwords(C, kH, kW)
     nbytes = int(lib().bnn_im2col_workspace_bytes(*geo))
-    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
-    _check(lib().bnn_im2col_packed(_ptr(x), *geo, _ptr(cols), _ptr(ws), nbytes, _stream()), "bnn_im2col_packed")
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
+    _check(lib().bnn_im2col_packed(_ptr(x), *geo, _ptr(cols), _ptr(workspace), workspace.numel(), _stream()),
+           "bnn_im2col_packed")
     return cols
 
 
