@@ -121,15 +121,20 @@ __device__ __forceinline__ void store_tile(const int (&acc)[TM][TN], int m0, int
   FastDiv divOHW;
   divOHW.d = kp->divOHW.d; divOHW.mul = kp->divOHW.mul; divOHW.shift = kp->divOHW.shift;
   // per-row affine constants once per tile (wave-uniform: scalar loads; rows past M re-read row M - 1)
+  typedef const float BNN_CONST_AS *cf32_ptr;
+  const cf32_ptr cscale = (cf32_ptr)(uintptr_t)scale, cbias = (cf32_ptr)(uintptr_t)bias;
   float scr[TM], bir[TM];
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     scr[i] = 1.0f;
     bir[i] = 0.0f;
-    if (Yp && axis == BNN_CH_ROW) {
+  }
+  if (Yp && axis == BNN_CH_ROW) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
       const int mi = min(m0 + i, M - 1);
-      scr[i] = scale[mi];
-      bir[i] = bias[mi];
+      scr[i] = cscale[mi];
+      bir[i] = cbias[mi];
     }
   }
 #pragma unroll
@@ -619,14 +624,28 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
     uint32_t bytes[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) bytes[j] = 0u;
+    // The affine constants of the wave's 8 rows: wave-uniform, read through the constant address
+    // space (scalar loads), all 16 requested before the first is used, rows past M re-reading row
+    // M - 1.  (Loaded row by row inside the loop below they were 16 dependent vector loads, each
+    // waited for: eight memory round trips at the end of every tile, during which the wave held
+    // its slot without issuing.)
+    typedef const float BNN_CONST_AS *cf32_ptr;
+    const cf32_ptr cscale = (cf32_ptr)(uintptr_t)scale, cbias = (cf32_ptr)(uintptr_t)bias;
+    float scr[TM], bir[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int mc = min(m0 + i, M - 1);
+      scr[i] = cscale[mc];
+      bir[i] = cbias[mc];
+    }
     // Rows run from the last to the first so that each sign is shifted in with one add-with-carry
     // (byte = 2 * byte + bit).  K - 2*acc decreases in acc: the 2x2 max is K - 2*min(acc).
 #pragma unroll
     for (int i = TM - 1; i >= 0; --i) {
       const int m = m0 + i;
       const bool row_ok = m < M;
-      const float sc = row_ok ? scale[m] : 0.0f;
-      const float bi = row_ok ? bias[m] : -1.0f;  // rows past M give bit 0
+      const float sc = row_ok ? scr[i] : 0.0f;
+      const float bi = row_ok ? bir[i] : -1.0f;  // rows past M give bit 0
       if (pool) {
         int a = acc[i][0];
 #pragma unroll
