@@ -11,7 +11,13 @@
 //     slice), so a layer with 16 tiles still occupies 256 waves and each wave walks 1/KS of K;
 //   * no LDS staging and no barrier in the loop: a lane gathers the chunk of its own column
 //     straight from the packed NHWC image (tap decode per 16-byte piece; taps outside the image
-//     are the "+1" pad word), two chunks ahead; A comes through scalar loads as everywhere else;
+//     are the "+1" pad word), two chunks ahead;
+//   * A does NOT come through scalar loads here: with four waves per SIMD nothing hides a scalar
+//     load's round trip to the L2, and it cannot be requested a chunk ahead (64 SGPRs per chunk).
+//     The workgroup copies its 32 rows of A into LDS once, with one round of vector loads that
+//     overlaps the first gathers, and every wave then reads its rows' chunk from LDS at one
+//     address for all lanes (a broadcast, free of bank conflicts); both xor operands are vector
+//     registers (last layer of the stack at batch 1: 12.7 -> 11.2 us, a whole pass 67 -> 63 us);
 //   * partial counts are additive (section 3.2: a sum over the reduction axis): the slices meet
 //     in LDS once, at the end, and the slice-0 waves run the epilogue -- int32 / fp32 NCHW, or
 //     the binarizing epilogue (optional 2x2 max-pool, affine map, sign) that writes packed NHWC;
@@ -21,7 +27,6 @@
 // Requires an even number of words per pixel (16-byte pieces never straddle a tap, rows end on a
 // chunk or half-chunk boundary); the host checks it.
 #include "common.h"
-#include "gemm_rows.inc"
 
 namespace bnn {
 
@@ -92,14 +97,20 @@ __global__ __launch_bounds__(256 * KS) void xnor_conv_latency_kernel(GemmParams 
     return v;
   };
 
-  // ---- A: this wave's 8 rows through scalar loads ---------------------------------------------------
-  const uint32_t arow_bytes = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)p.lda32 * 4u));
-  const uint32_t aoff_max = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(p.M - 1) * (uint32_t)p.lda32 * 4u));
-  const uint32_t aoff_first = (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)min(m0, p.M - 1) * (uint32_t)p.lda32 * 4u));
-  const uint32_t Abase_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(uintptr_t)p.A);
-  const uint32_t Abase_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)((uintptr_t)p.A >> 32));
-  const uint64_t Abase0 = ((uint64_t)Abase_hi << 32) | (uint64_t)Abase_lo;
-#define BNN_LAT_AOFF(i) min(aoff_first + (uint32_t)(i) * arow_bytes, aoff_max)
+  // ---- A: the tile's 32 rows, copied to LDS once (rows past M re-read row M - 1) --------------------
+  extern __shared__ __attribute__((aligned(16))) uint32_t sA[];  // [32][2 * Kw64] dwords
+  {
+    const int ppr = p.Kw64 >> 1;  // 16-byte pieces per row (Kw64 is even)
+    const char *Ab = reinterpret_cast<const char *>(p.A);
+    for (int idx = tid; idx < 32 * ppr; idx += 256 * KS) {
+      const int row = idx / ppr, pc = idx - row * ppr;
+      const int m = min(mi * 32 + row, p.M - 1);
+      const u32x4 v = *reinterpret_cast<const u32x4 *>(Ab + (size_t)m * (size_t)p.lda32 * 4u + (size_t)pc * 16u);
+      *reinterpret_cast<u32x4 *>(&sA[row * 2 * p.Kw64 + pc * 4]) = v;
+    }
+  }
+  const uint32_t *sArow = &sA[(wm * 8) * 2 * p.Kw64];
+  const int arow = 2 * p.Kw64;  // dwords per row in LDS
 
   int acc[8][1];
 #pragma unroll
@@ -116,24 +127,39 @@ __global__ __launch_bounds__(256 * KS) void xnor_conv_latency_kernel(GemmParams 
     b.lo = gather_piece(2 * c);
     b.hi = gather_piece(2 * c + 1);
   };
+  // acc += popcount(x) as one instruction (the optimizer otherwise splits it into a popcount and an add)
+  auto popc_acc = [](uint32_t x, int a) {
+    asm("v_bcnt_u32_b32 %0, %1, %0" : "+v"(a) : "v"(x));
+    return a;
+  };
   auto compute = [&](const u32x8 &bv, int cl) {
-    const uint64_t Abase = Abase0 + (uint64_t)(uint32_t)(cb + cl) * 32u;
-    u32x8 a[8];
+    const uint32_t *ac = sArow + (cb + cl) * 8;
+    // two rows of A in flight at a time: more would not fit the 128 registers a 1024-thread workgroup leaves a lane
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-      asm volatile("s_load_dwordx8 %0, %1, %2" : "=s"(a[i]) : "s"(Abase), "s"(BNN_LAT_AOFF(i)));
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+s"(a[0]), "+s"(a[1]), "+s"(a[2]), "+s"(a[3]), "+s"(a[4]), "+s"(a[5]), "+s"(a[6]), "+s"(a[7]));
-    uint32_t t0, t1;
-#define BNN_BV(j, d) bv[d]
+    for (int i = 0; i < 8; i += 2) {
+      const u32x4 a0 = *reinterpret_cast<const u32x4 *>(ac + i * arow);
+      const u32x4 a1 = *reinterpret_cast<const u32x4 *>(ac + i * arow + 4);
+      const u32x4 c0 = *reinterpret_cast<const u32x4 *>(ac + (i + 1) * arow);
+      const u32x4 c1 = *reinterpret_cast<const u32x4 *>(ac + (i + 1) * arow + 4);
+      int t = acc[i][0], u = acc[i + 1][0];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) BNN_GEMM_ROW_1_NY(acc[i], a[i], BNN_BV, t0, t1);
-#undef BNN_BV
+      for (int d = 0; d < 4; ++d) t = popc_acc(a0[d] ^ bv[d], t);
+#pragma unroll
+      for (int d = 0; d < 4; ++d) t = popc_acc(a1[d] ^ bv[4 + d], t);
+#pragma unroll
+      for (int d = 0; d < 4; ++d) u = popc_acc(c0[d] ^ bv[d], u);
+#pragma unroll
+      for (int d = 0; d < 4; ++d) u = popc_acc(c1[d] ^ bv[4 + d], u);
+      acc[i][0] = t;
+      acc[i + 1][0] = u;
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
   u32x8 bq[DEPTH];
 #pragma unroll
   for (int d = 0; d < DEPTH; ++d)
     if (d < nfull) load_b(bq[d], d);
+  __syncthreads();  // the copy of A is complete (its loads and the first gathers were in flight together)
   int c = 0;
   for (; c + DEPTH <= nfull; c += DEPTH) {
 #pragma unroll
@@ -148,20 +174,16 @@ __global__ __launch_bounds__(256 * KS) void xnor_conv_latency_kernel(GemmParams 
   // the half chunk (last two words), by the last slice
   if (has_half && ks == KS - 1) {
     const u32x4 bv = gather_piece(2 * nfull_all);
-    const uint64_t Abase = Abase0 + (uint64_t)(uint32_t)nfull_all * 32u;
-    u32x4 a[8];
+    const uint32_t *ac = sArow + nfull_all * 8;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-      asm volatile("s_load_dwordx4 %0, %1, %2" : "=s"(a[i]) : "s"(Abase), "s"(BNN_LAT_AOFF(i)));
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+s"(a[0]), "+s"(a[1]), "+s"(a[2]), "+s"(a[3]), "+s"(a[4]), "+s"(a[5]), "+s"(a[6]), "+s"(a[7]));
-    uint32_t t0, t1;
-#define BNN_BV(j, d) bv[d]
+    for (int i = 0; i < 8; ++i) {
+      const u32x4 a0 = *reinterpret_cast<const u32x4 *>(ac + i * arow);
+      int t = acc[i][0];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) BNN_GEMM_HALF_1_NY(acc[i], a[i], BNN_BV, t0, t1);
-#undef BNN_BV
+      for (int d = 0; d < 4; ++d) t = popc_acc(a0[d] ^ bv[d], t);
+      acc[i][0] = t;
+    }
   }
-#undef BNN_LAT_AOFF
 
   // ---- slices meet in LDS ----------------------------------------------------------------------------
 #pragma unroll
@@ -178,6 +200,22 @@ __global__ __launch_bounds__(256 * KS) void xnor_conv_latency_kernel(GemmParams 
     }
     if constexpr (EMODE == 0) {
       // int32 and / or fp32, NCHW (columns are pixels in NHWC order: n -> image, pixel)
+      typedef const float __attribute__((address_space(4))) *cf32_ptr;
+      const cf32_ptr cscale = (cf32_ptr)(uintptr_t)p.scale, cbias = (cf32_ptr)(uintptr_t)p.bias;
+      float scr[8], bir[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        scr[i] = 1.0f;
+        bir[i] = 0.0f;
+      }
+      if (p.Y) {  // wave-uniform scalar loads, requested together; rows past M re-read row M - 1
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int mc = min(m0 + i, p.M - 1);
+          scr[i] = cscale[mc];
+          bir[i] = cbias[mc];
+        }
+      }
       if (col_ok) {
         const uint32_t im = fdiv((uint32_t)n, p.divOHW);
         const uint32_t pix = (uint32_t)n - im * p.OHW;
@@ -188,7 +226,7 @@ __global__ __launch_bounds__(256 * KS) void xnor_conv_latency_kernel(GemmParams 
             const int v = p.Kformula - 2 * tot[i];
             const int64_t off = (int64_t)im * p.img_stride + pix;
             if (p.C) p.C[off + (int64_t)m * p.ldc] = v;
-            if (p.Y) p.Y[off + (int64_t)m * p.ldy] = fmaf(p.scale[m], (float)v, p.bias[m]);
+            if (p.Y) p.Y[off + (int64_t)m * p.ldy] = fmaf(scr[i], (float)v, bir[i]);
           }
         }
       }
@@ -196,13 +234,23 @@ __global__ __launch_bounds__(256 * KS) void xnor_conv_latency_kernel(GemmParams 
       // binarizing epilogue: K - 2*acc decreases in acc, so the 2x2 max is K - 2*min(acc) over the
       // four neighbouring lanes of a window; rows run from the last to the first so that each sign
       // is shifted in with one add
+      // the 8 rows' affine constants: wave-uniform scalar loads, requested together
+      typedef const float __attribute__((address_space(4))) *cf32_ptr;
+      const cf32_ptr cscale = (cf32_ptr)(uintptr_t)p.scale, cbias = (cf32_ptr)(uintptr_t)p.bias;
+      float scr[8], bir[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int mc = min(m0 + i, p.M - 1);
+        scr[i] = cscale[mc];
+        bir[i] = cbias[mc];
+      }
       uint32_t byte = 0u;
 #pragma unroll
       for (int i = 7; i >= 0; --i) {
         const int m = m0 + i;
         const bool row_ok = m < p.M;
-        const float sc = row_ok ? p.scale[m] : 0.0f;
-        const float bi = row_ok ? p.bias[m] : -1.0f;  // rows past M give bit 0
+        const float sc = row_ok ? scr[i] : 0.0f;
+        const float bi = row_ok ? bir[i] : -1.0f;  // rows past M give bit 0
         int a = tot[i];
         if (g.pool) {
           a = min(a, __shfl_xor(a, 1));
@@ -238,6 +286,8 @@ bool latency_applicable(const GemmParams &p) {
   if (p.Kw64 != p.g.kH * p.g.kW * p.g.Cw) return false;
   if ((int64_t)p.M * p.lda32 * 4 > 0xffffffffLL) return false;
   if (p.g.pool && (p.N & 3)) return false;
+  if (p.lda32 != 2 * p.Kw64) return false;                    // rows of A contiguous: 16-byte aligned row starts
+  if ((int64_t)32 * p.Kw64 * 8 > 24 * 1024) return false;     // the tile's rows of A must fit the LDS left beside the partial sums
   return true;
 }
 
@@ -248,12 +298,13 @@ bnn_status launch_latency(GemmParams &p, int emode, int ks, hipStream_t s) {
   if (tiles > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
   ProfScope ps(KID_XNOR_CONV_LATENCY, s);
   const dim3 grid((unsigned)tiles);
+  const size_t lds = (size_t)32 * p.Kw64 * 8;  // the tile's rows of A
   if (ks == 4) {
-    if (emode == 1) hipLaunchKernelGGL((xnor_conv_latency_kernel<4, 1>), grid, dim3(1024), 0, s, p);
-    else hipLaunchKernelGGL((xnor_conv_latency_kernel<4, 0>), grid, dim3(1024), 0, s, p);
+    if (emode == 1) hipLaunchKernelGGL((xnor_conv_latency_kernel<4, 1>), grid, dim3(1024), lds, s, p);
+    else hipLaunchKernelGGL((xnor_conv_latency_kernel<4, 0>), grid, dim3(1024), lds, s, p);
   } else {
-    if (emode == 1) hipLaunchKernelGGL((xnor_conv_latency_kernel<2, 1>), grid, dim3(512), 0, s, p);
-    else hipLaunchKernelGGL((xnor_conv_latency_kernel<2, 0>), grid, dim3(512), 0, s, p);
+    if (emode == 1) hipLaunchKernelGGL((xnor_conv_latency_kernel<2, 1>), grid, dim3(512), lds, s, p);
+    else hipLaunchKernelGGL((xnor_conv_latency_kernel<2, 0>), grid, dim3(512), lds, s, p);
   }
   return launch_status();
 }

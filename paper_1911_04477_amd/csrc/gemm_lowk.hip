@@ -140,6 +140,23 @@ __global__ __launch_bounds__(256) void xnor_gemm_lowk_kernel(GemmParams p) {
       for (int i = 0; i < 8; ++i) BNN_GEMM_ROW_4(acc[i], a[i], BNN_BV, t0, t1);
     }
 #undef BNN_BV
+    // per-row affine constants of this group: wave-uniform scalar loads, requested together
+    float scr[8], bir[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      scr[i] = 1.0f;
+      bir[i] = 0.0f;
+    }
+    if (p.Y && p.axis == BNN_CH_ROW) {
+      typedef const float __attribute__((address_space(4))) *cf32_ptr;
+      const cf32_ptr cscale = (cf32_ptr)(uintptr_t)p.scale, cbias = (cf32_ptr)(uintptr_t)p.bias;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int mc = min(m0 + i, p.M - 1);
+        scr[i] = cscale[mc];
+        bir[i] = cbias[mc];
+      }
+    }
     if (!col_ok) continue;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -152,9 +169,8 @@ __global__ __launch_bounds__(256) void xnor_gemm_lowk_kernel(GemmParams p) {
       if (p.Y) {
         f32x4 y;
         if (p.axis == BNN_CH_ROW) {
-          const float s1 = p.scale[m], b1 = p.bias[m];  // wave-uniform
 #pragma unroll
-          for (int j = 0; j < 4; ++j) y[j] = fmaf(s1, (float)v[j], b1);
+          for (int j = 0; j < 4; ++j) y[j] = fmaf(scr[i], (float)v[j], bir[i]);
         } else {
 #pragma unroll
           for (int j = 0; j < 4; ++j) y[j] = fmaf(csc[j], (float)v[j], cbi[j]);
