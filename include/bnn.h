@@ -188,7 +188,9 @@ BNN_API size_t bnn_conv2d_workspace_bytes(int N, int C, int H, int W, int kH, in
  *     streams, two threads) race on it and must be serialised by the caller.  The array keeps the
  *     previous call's contents; every word a call reads it has written first, so nothing needs
  *     clearing.
- *   - BNN_ERR_HIP if the array's device address cannot be obtained.
+ *   - The first call on a device looks up the array's device address (once per device, kept for
+ *     the life of the process); make that first call outside a stream capture.  BNN_ERR_HIP if
+ *     the address cannot be obtained.
  */
 #define BNN_CONV2D_NOALLOC_MAX_BYTES (8u << 20)
 BNN_API bnn_status bnn_conv2d_noalloc(const float *x, const uint64_t *w_packed, int N, int C, int H, int W,
