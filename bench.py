@@ -647,23 +647,33 @@ def main():
         s2 = e0.elapsed_time(e1) / 1e3
         line["two_half_batches_on_two_streams"] = {"ms_per_step": round(s2 / args.steps * 1e3, 4),
                                                    "TBOPS": round(wl["bops"] / (s2 / args.steps) / 1e12, 3)}
+    def side(name, fn):
+        # a side measurement must never cost the line its headline figures
+        try:
+            line[name] = fn()
+        except Exception as e:  # noqa: BLE001
+            line[name] = {"error": f"{type(e).__name__}: {e}"[:300]}
+            print(f"bench.py: side measurement {name} failed: {e}", file=sys.stderr)
+
     if (args.steps < 200 or args.warmup < 100) and not args.no_sustained:
         # the same step after the clocks have settled (a few hundred steps of continuous work)
-        s3, _ = time_steps(wl["fn"], 1000, 200)
-        line["sustained"] = {"steps": 1000, "warmup": 200, "ms_per_step": round(s3 / 1000 * 1e3, 4),
-                             "value": round(wl["bops"] / (s3 / 1000) / 1e12, 3)}
+        def sustained():
+            s3, _ = time_steps(wl["fn"], 1000, 200)
+            return {"steps": 1000, "warmup": 200, "ms_per_step": round(s3 / 1000 * 1e3, 4),
+                    "value": round(wl["bops"] / (s3 / 1000) / 1e12, 3)}
+        side("sustained", sustained)
     if not args.no_extras:
-        line["streaming"] = side_measurements()
+        side("streaming", side_measurements)
         line["hbm_peak_GBs"] = HBM_PEAK_GBS
         if args.workload == "cfg4" and args.stack == "fused":
-            line["unfused_stack"] = unfused_stack(args)
+            side("unfused_stack", lambda: unfused_stack(args))
             if args.reading == "A":
-                line["reading_B_fused_stack"] = reading_b_step(args)
+                side("reading_B_fused_stack", lambda: reading_b_step(args))
             if not args.no_graphs:
-                line["small_batch_latency"] = small_batch_latency(args)
-        line["other_configs"] = other_configs(args)
-        line["mfma_ablation"] = mfma_ablation()
-        line["control_group"] = control_group()
+                side("small_batch_latency", lambda: small_batch_latency(args))
+        side("other_configs", lambda: other_configs(args))
+        side("mfma_ablation", mfma_ablation)
+        side("control_group", control_group)
     print(json.dumps(line), flush=True)
 
 
