@@ -840,3 +840,55 @@ def test_conv2d_f32_real_valued_layer(case, affine):
     # injected infinities of both signs meet in some sums: NaN there on both sides
     assert np.array_equal(np.isnan(got), np.isnan(ref))
     assert np.array_equal(got, ref, equal_nan=True)
+
+
+# ---------------------------------------------------------------- whatever the size heuristic picks
+def test_heuristic_kernel_selection_on_random_gemm_shapes():
+    """Seeded random (M, N, K) on and off every grid through the entry points as an application
+    calls them: the host chooses between the throughput, one-wave, split-K and short-row kernels."""
+    rng = np.random.default_rng(1234)
+    done = 0
+    while done < 80:
+        M = int(rng.choice([1, 3, 8, 31, 32, 33, 64, 100, 256, 300, 513]))
+        N = int(rng.choice([1, 4, 60, 64, 68, 128, 200, 256, 1000, 1024, 4100]))
+        K = int(rng.choice([1, 64, 65, 128, 200, 256, 257, 1000, 2048, 4096, 4100, 8192]))
+        if M * N * K > 2e9:
+            continue
+        done += 1
+        print(f"heuristic gemm M={M} N={N} K={K}", flush=True)
+        A = rng.standard_normal((M, K)).astype(np.float32)
+        Bm = rng.standard_normal((N, K)).astype(np.float32)
+        sc = ((rng.random(N) + 0.5) * rng.choice([-1.0, 1.0], N)).astype(np.float32)
+        bi = rng.standard_normal(N).astype(np.float32)
+        C, Y = B.bnn_xnor_gemm_epilogue(B.bnn_encode(dev(A)), B.bnn_encode(dev(Bm)), K, dev(sc), dev(bi), B.CH_COL,
+                                        want_int=True)
+        ref = oracle.gemm_pm1(A, Bm)
+        assert np.array_equal(host(C), ref), (M, N, K)
+        assert np.array_equal(host(Y), oracle.scale_bias(ref, sc, bi, "col")), (M, N, K)
+
+
+def test_heuristic_kernel_selection_on_random_packed_convs():
+    """Seeded random layer shapes (few to many output pixels, scales of both signs) through
+    bnn_conv2d_packed as the stack calls it: latency form, throughput tiles, short-row kernel."""
+    rng = np.random.default_rng(4321)
+    for it in range(60):
+        N = int(rng.integers(1, 9))
+        C = int(rng.choice([64, 128, 130, 192, 256, 512]))
+        H, W = int(rng.choice([4, 6, 8, 10, 16])), int(rng.choice([4, 6, 8, 12, 16]))
+        D = int(rng.choice([8, 31, 32, 33, 64, 100, 128, 256]))
+        k = int(rng.choice([1, 3]))
+        p = k // 2
+        shape = inputs.ConvShape(N, C, H, W, D, k, k, 1, 1, p, p)
+        print(f"heuristic conv {shape}", flush=True)
+        d = inputs.conv_inputs(shape, seed=1000 + it)
+        sc = (d["scale"] * rng.choice([-1.0, 1.0], D)).astype(np.float32)
+        xp = _u64dev(oracle.pack_nhwc(d["x"]))
+        wp = B.bnn_pack_conv_weight(dev(d["w"]))
+        ref = oracle.conv2d_pm1(d["x"], d["w"], (1, 1), (p, p))
+        assert np.array_equal(host(B.bnn_conv2d_packed(xp, wp, C, D, k, k, (1, 1), (p, p), out="i32")), ref)
+        got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, k, k, (1, 1), (p, p), scale=dev(sc), bias=dev(d["bias"]),
+                                         out="packed"))
+        assert np.array_equal(got, oracle.pack_nhwc(oracle.scale_bias(ref, sc, d["bias"], "nchw")))
+        got = as_u64(B.bnn_conv2d_packed(xp, wp, C, D, k, k, (1, 1), (p, p), pool=2, scale=dev(sc),
+                                         bias=dev(d["bias"]), out="packed"))
+        assert np.array_equal(got, oracle.pack_nhwc(oracle.scale_bias(oracle.maxpool2x2_i32(ref), sc, d["bias"], "nchw")))
