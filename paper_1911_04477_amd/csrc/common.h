@@ -104,6 +104,7 @@ struct GemmParams {
   int tilesM, tilesN;
   int prio_from;       // workgroups with id >= prio_from lower their wave priority as they advance through K
   int n_cu;            // compute units of the device (host only: launch heuristics)
+  int nt_store;        // int32 / fp32 tile stores are line-aligned: use non-temporal stores
   ConvGeom g;          // implicit B only
   uint64_t *outp;      // packed-sign output [pixels, cw_out] (packed epilogue only)
   int cw_out;

@@ -118,6 +118,10 @@ __device__ __forceinline__ void store_tile(const int (&acc)[TM][TN], int m0, int
   float *const Yp = kp->Y;
   const int64_t ldc = kp->ldc, ldy = kp->ldy, img_stride = kp->img_stride;
   const uint32_t OHW = kp->OHW;
+  // Non-temporal stores when every 256-byte piece a wave stores covers whole 128-byte lines (measured
+  // 1 % faster then); ordinary stores otherwise, so that pieces that share a line meet in the L2
+  // instead of each going to memory as a partial line (49.6 -> 40.7 us on a 31 x 33 map).
+  const bool nt = kp->nt_store != 0;
   FastDiv divOHW;
   divOHW.d = kp->divOHW.d; divOHW.mul = kp->divOHW.mul; divOHW.shift = kp->divOHW.shift;
   // per-row affine constants once per tile (wave-uniform: scalar loads; rows past M re-read row M - 1)
@@ -156,10 +160,15 @@ __device__ __forceinline__ void store_tile(const int (&acc)[TM][TN], int m0, int
     for (int i = 0; i < TM; ++i) {
       if (m0 + i < M) {
         const int v = Kformula - 2 * acc[i][j];
-        if (cp) __builtin_nontemporal_store(v, cp);
+        if (cp) {
+          if (nt) __builtin_nontemporal_store(v, cp);
+          else *cp = v;
+        }
         if (yp) {
           const float s1 = axis == BNN_CH_ROW ? scr[i] : sc, b1 = axis == BNN_CH_ROW ? bir[i] : bi;
-          __builtin_nontemporal_store(fmaf(s1, (float)v, b1), yp);
+          const float y = fmaf(s1, (float)v, b1);
+          if (nt) __builtin_nontemporal_store(y, yp);
+          else *yp = y;
         }
       }
       if (cp) cp += ldc;
@@ -1093,6 +1102,12 @@ static bnn_status launch_splitk_by(GemmParams &p, int tmg, int ks, hipStream_t s
 bnn_status run_gemm(GemmParams &p, int bmode, int emode, hipStream_t s, const GemmTune &tune) {
   int cfg = tune.cfg;
   p.n_cu = device_cu_count();
+  {
+    const bool planes = p.img_stride != 0;
+    const bool c_ok = !p.C || (((uintptr_t)p.C & 127u) == 0 && (planes ? (p.OHW % 32u) == 0 : (p.ldc % 32) == 0));
+    const bool y_ok = !p.Y || (((uintptr_t)p.Y & 127u) == 0 && (planes ? (p.OHW % 32u) == 0 : (p.ldy % 32) == 0));
+    p.nt_store = (c_ok && y_ok) ? 1 : 0;
+  }
   const int64_t full = 2 * (int64_t)p.n_cu;  // tiles that give every compute unit two workgroups
   if (bmode == 1 && emode == 0 && p.g.pool == 0 && p.g.kH == 1 && p.g.kW == 1 && p.g.sH == 1 && p.g.sW == 1 &&
       p.g.pH == 0 && p.g.pW == 0) {
