@@ -424,7 +424,8 @@ def small_batch_latency(args):
 
 
 def mfma_ablation():
-    """The int8 and fp4 MFMA-on-0/1 ablations beside the VALU GEMM on the GEMM view of cfg 5a and cfg 3."""
+    """The MFMA ablations beside the VALU GEMM on the GEMM view of cfg 5a and cfg 3: int8 and fp4 with the
+    bits expanded on the fly, and fp4 on operands kept expanded in memory (the expansion timed apart)."""
     import torch
     from paper_1911_04477_amd import binding as B
     dev = "cuda:0"
@@ -437,16 +438,27 @@ def mfma_ablation():
         C = torch.empty((M, N), dtype=torch.int32, device=dev)
         C2 = torch.empty((M, N), dtype=torch.int32, device=dev)
         C3 = torch.empty((M, N), dtype=torch.int32, device=dev)
+        C4 = torch.empty((M, N), dtype=torch.int32, device=dev)
+        A4, B4 = B.bnn_expand_fp4(A, K), B.bnn_expand_fp4(Bm, K)
         tv, _ = time_steps(lambda: B.bnn_xnor_gemm(A, Bm, K, C), 200, 100)
         tm, _ = time_steps(lambda: B.bnn_xnor_gemm_mfma_i8(A, Bm, K, C2), 200, 100)
         t4, _ = time_steps(lambda: B.bnn_xnor_gemm_mfma_fp4(A, Bm, K, C3), 200, 100)
+        tx, _ = time_steps(lambda: B.bnn_xnor_gemm_mfma_fp4_expanded(A4, B4, K, C4), 200, 100)
+        te, _ = time_steps(lambda: B.bnn_expand_fp4(Bm, K, out=B4), 200, 100)
         bops = 2.0 * M * N * K
+        moved = A4.numel() + B4.numel() + 4 * M * N   # bytes the expanded form reads and writes once
         out[name] = {"valu_TBOPS": round(bops / (tv / 200) / 1e12, 1), "mfma_i8_TBOPS": round(bops / (tm / 200) / 1e12, 1),
                      "mfma_fp4_TBOPS": round(bops / (t4 / 200) / 1e12, 1),
-                     "bit_identical": bool((C == C2).all().item() and (C == C3).all().item()),
+                     "mfma_fp4_expanded_TBOPS": round(bops / (tx / 200) / 1e12, 1),
+                     "bit_identical": bool((C == C2).all().item() and (C == C3).all().item()
+                                           and (C == C4).all().item()),
                      "mfma_i8_frac_of_int8_dense_peak": round(bops / (tm / 200) / 5.0e15, 4),
-                     "mfma_fp4_frac_of_fp4_dense_peak": round(bops / (t4 / 200) / 10.1e15, 4)}
-        del A, Bm, C, C2, C3
+                     "mfma_fp4_frac_of_fp4_dense_peak": round(bops / (t4 / 200) / 10.1e15, 4),
+                     "mfma_fp4_expanded_frac_of_fp4_dense_peak": round(bops / (tx / 200) / 10.1e15, 4),
+                     "mfma_fp4_expanded_GBs": round(moved / (tx / 200) / 1e9, 1),
+                     "expand_B_us": round(te / 200 * 1e6, 1),
+                     "expand_B_GBs": round((Bm.numel() * 8 + B4.numel()) / (te / 200) / 1e9, 1)}
+        del A, Bm, C, C2, C3, C4, A4, B4
     return out
 
 

@@ -295,6 +295,30 @@ BNN_API bnn_status bnn_xnor_gemm_mfma_fp4(const uint64_t *A, int64_t lda, const 
                                           int32_t *C, int64_t ldc, int64_t M, int64_t N, int64_t K,
                                           void *stream);
 
+/*
+ * bnn_expand_fp4, bnn_xnor_gemm_mfma_fp4_expanded -- third ABLATION: the matrix-core GEMM with the
+ * expansion taken out of it.  The two forms above spend most of their time turning bits into
+ * matrix operands; here that is a separate streaming pass, and the GEMM reads operands kept in
+ * memory at 4 bits per value.
+ *   E2M1 row format: value k of a row is the 4-bit floating-point code of +1.0 (0x2) or -1.0
+ *   (0xA) in nibble k % 2 (low nibble first) of byte k / 2; the row is padded with the code of
+ *   0.0 (0x0) to a multiple of 64 values, bnn_fp4_row_bytes(K) = 32 * ceil(K / 64) bytes.
+ * bnn_expand_fp4: src [rows, src_ld] packed sign words (device, read; bits past K ignored),
+ *   dst [rows, dst_ld_bytes] bytes (device, written), dst_ld_bytes >= bnn_fp4_row_bytes(K) and a
+ *   multiple of 16.  Both 16-byte aligned.
+ * bnn_xnor_gemm_mfma_fp4_expanded: A4 [M, lda_bytes], B4 [N, ldb_bytes] in that format (device,
+ *   read), C [M, ldc] int32 (device, written) = sum over k of a_k * b_k, the same number as
+ *   bnn_xnor_gemm gives on the packed rows (section 3.2), exact in the fp32 accumulator of
+ *   V_MFMA_SCALE_F32_32X32X64_F8F6F4 for K below 2^24 (BNN_ERR_UNSUPPORTED beyond).
+ * Errors as bnn_xnor_gemm; strides in bytes, multiples of 16.  Not used by any other entry point.
+ */
+BNN_API int64_t bnn_fp4_row_bytes(int64_t K);
+BNN_API bnn_status bnn_expand_fp4(const uint64_t *src, int64_t rows, int64_t K, int64_t src_ld, uint8_t *dst,
+                                  int64_t dst_ld_bytes, void *stream);
+BNN_API bnn_status bnn_xnor_gemm_mfma_fp4_expanded(const uint8_t *A4, int64_t lda_bytes, const uint8_t *B4,
+                                                   int64_t ldb_bytes, int32_t *C, int64_t ldc, int64_t M,
+                                                   int64_t N, int64_t K, void *stream);
+
 /* ---- control group --------------------------------------------------------------------- */
 
 /*

@@ -57,6 +57,15 @@ BNN_API bnn_status bnn_testing_conv2d_packed(const uint64_t *x_packed, const uin
                                              const float *scale, const float *bias, int cfg, int lean,
                                              void *stream);
 
+/*
+ * bnn_xnor_gemm_mfma_fp4_expanded on a chosen workgroup tile (rows x columns of C):
+ *   -1 the choice of bnn.h's entry point;  0 128 x 128;  1 256 x 128;  2 128 x 256.
+ * Other values: BNN_ERR_SHAPE.
+ */
+BNN_API bnn_status bnn_testing_xnor_gemm_mfma_fp4_expanded(const uint8_t *A4, int64_t lda_bytes, const uint8_t *B4,
+                                                           int64_t ldb_bytes, int32_t *C, int64_t ldc, int64_t M,
+                                                           int64_t N, int64_t K, int tile, void *stream);
+
 /* ---- measurement helpers ------------------------------------------------------------ */
 
 /*

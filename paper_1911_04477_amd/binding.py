@@ -33,6 +33,9 @@ SIGNATURES = {
     "bnn_xnor_gemm": (_i32, [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _p]),
     "bnn_xnor_gemm_mfma_i8": (_i32, [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _p]),
     "bnn_xnor_gemm_mfma_fp4": (_i32, [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _p]),
+    "bnn_fp4_row_bytes": (_i64, [_i64]),
+    "bnn_expand_fp4": (_i32, [_p, _i64, _i64, _i64, _p, _i64, _p]),
+    "bnn_xnor_gemm_mfma_fp4_expanded": (_i32, [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _p]),
     "bnn_control_conv2d_f32": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p]),
     "bnn_xnor_gemm_epilogue": (_i32, [_p, _i64, _p, _i64, _i64, _i64, _i64, _p, _i64, _p, _i64, _p, _p, _i32, _p]),
     "bnn_conv2d": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p, _p, _p, _p, _sz, _p]),
@@ -54,6 +57,7 @@ TESTING_SIGNATURES = {
                                               _i32, _p]),
     "bnn_testing_conv2d": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p, _p, _p, _p, _sz, _i32, _i32, _p]),
     "bnn_testing_conv2d_packed": (_i32, [_p, _p] + [_i32] * 12 + [_p, _p, _p, _p, _p, _i32, _i32, _p]),
+    "bnn_testing_xnor_gemm_mfma_fp4_expanded": (_i32, [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _i32, _p]),
     "bnn_prof_enable": (_i32, [_i32]),
     "bnn_prof_reset": (_i32, []),
     "bnn_prof_count": (_i64, []),
@@ -217,6 +221,39 @@ def bnn_xnor_gemm_mfma_fp4(A: torch.Tensor, B: torch.Tensor, K: int, C: Optional
     ldb = B.stride(0) if N > 1 else max(B.shape[1], 1)
     _check(lib().bnn_xnor_gemm_mfma_fp4(_ptr(A), lda, _ptr(B), ldb, _ptr(C), C.stride(0) if M > 1 else max(N, 1), M, N,
                                         K, _stream()), "bnn_xnor_gemm_mfma_fp4")
+    return C
+
+
+def bnn_expand_fp4(packed: torch.Tensor, K: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Ablation: packed sign rows [rows, >= ceil(K/64)] int64 -> E2M1 rows [rows, 32 * ceil(K/64)] uint8."""
+    _dev(packed, torch.int64, "packed")
+    rows = packed.shape[0]
+    rb = int(lib().bnn_fp4_row_bytes(K))
+    if out is None:
+        out = torch.empty((rows, rb), dtype=torch.uint8, device=packed.device)
+    src_ld = packed.stride(0) if rows > 1 else max(packed.shape[1], 1)
+    dst_ld = out.stride(0) if rows > 1 else max(out.shape[1], 16)
+    _check(lib().bnn_expand_fp4(_ptr(packed), rows, K, src_ld, _ptr(out), dst_ld, _stream()), "bnn_expand_fp4")
+    return out
+
+
+def bnn_xnor_gemm_mfma_fp4_expanded(A4: torch.Tensor, B4: torch.Tensor, K: int, C: Optional[torch.Tensor] = None,
+                                    tile: Optional[int] = None) -> torch.Tensor:
+    """Ablation: the binarized GEMM on operands kept in memory as E2M1 +-1 rows (bnn_expand_fp4)."""
+    _dev(A4, torch.uint8, "A4")
+    _dev(B4, torch.uint8, "B4")
+    M, N = A4.shape[0], B4.shape[0]
+    if C is None:
+        C = torch.empty((M, N), dtype=torch.int32, device=A4.device)
+    lda = A4.stride(0) if M > 1 else max(A4.shape[1], 16)
+    ldb = B4.stride(0) if N > 1 else max(B4.shape[1], 16)
+    ldc = C.stride(0) if M > 1 else max(N, 1)
+    if tile is None:
+        _check(lib().bnn_xnor_gemm_mfma_fp4_expanded(_ptr(A4), lda, _ptr(B4), ldb, _ptr(C), ldc, M, N, K, _stream()),
+               "bnn_xnor_gemm_mfma_fp4_expanded")
+    else:
+        _check(lib().bnn_testing_xnor_gemm_mfma_fp4_expanded(_ptr(A4), lda, _ptr(B4), ldb, _ptr(C), ldc, M, N, K, tile,
+                                                             _stream()), "bnn_testing_xnor_gemm_mfma_fp4_expanded")
     return C
 
 

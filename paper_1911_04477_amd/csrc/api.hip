@@ -116,6 +116,8 @@ extern "C" const char *bnn_kernel_name(int kernel_id) {
     case bnn::KID_XNOR_CONV_LATENCY: return "xnor_conv_latency";
     case bnn::KID_XNOR_GEMM_MFMA: return "xnor_gemm_mfma_i8";
     case bnn::KID_XNOR_GEMM_MFMA_FP4: return "xnor_gemm_mfma_fp4";
+    case bnn::KID_XNOR_GEMM_MFMA_FP4X: return "xnor_gemm_mfma_fp4_expanded";
+    case bnn::KID_EXPAND_FP4: return "expand_fp4";
     case bnn::KID_CONTROL_CONV_F32: return "control_conv_f32";
     case bnn::KID_MAXPOOL: return "maxpool2x2";
     case bnn::KID_CONV_F32: return "conv2d_f32";

@@ -26,7 +26,9 @@ enum KernelId : int {
   KID_XNOR_GEMM_MFMA_FP4 = 14,
   KID_XNOR_GEMM_LOWK = 15,
   KID_XNOR_CONV_LATENCY = 16,
-  KID_COUNT = 17
+  KID_EXPAND_FP4 = 17,
+  KID_XNOR_GEMM_MFMA_FP4X = 18,
+  KID_COUNT = 19
 };
 
 // Timing hook: records an event pair around a launch when profiling is on.

@@ -13,6 +13,7 @@
 // conflict-free 16-byte accesses).  Each wave multiplies a 64 x 64 sub-tile: 2 x 2 blocks of
 // 32 x 32, two K-steps of 32 per chunk.
 #include "common.h"
+#include "bnn_testing.h"
 
 namespace bnn {
 
@@ -269,6 +270,187 @@ __global__ __launch_bounds__(256, 2) void xnor_gemm_mfma_fp4_kernel(MfmaParams p
     }
 }
 
+// ---- third form: operands kept expanded in memory ---------------------------------------------
+// Both forms above spend most of their time expanding bits.  Here the expansion is a separate
+// streaming pass (a layer's epilogue could write this format itself): a row of K binary values is
+// stored as K E2M1 codes, +1.0 (0x2) or -1.0 (0xA), value k in nibble k % 2 of byte k / 2, padded
+// with 0.0 (0x0) to a multiple of 64 values, i.e. 4 bits per value.  The matrix instruction then
+// computes sum_k a_k * b_k directly: the result itself, exact in fp32 for K < 2^24, with no
+// popcount correction, and the pad values contribute nothing.
+//
+// Workgroup: 4 waves as 2 x 2, each wave WTM x WTN blocks of 32 x 32 (2 x 2, 4 x 2 or 2 x 4; with
+// 4 x 4 the accumulators alone fill the register file and the compiler spills); K consumed KCH
+// values at a time through double-buffered LDS.  A chunk of a row is KCH / 2 bytes, stored with 16 bytes of
+// padding, so that the 16-byte reads of eight consecutive rows cover all banks.
+struct Fp4xParams {
+  const uint8_t *A, *B;
+  int64_t lda, ldb, ldc;  // lda, ldb in bytes
+  int32_t *C;
+  int M, N;
+  int pieces;  // 16-byte pieces per row: 2 * ceil(K / 64)
+  int tilesM;
+};
+
+template <int WTM, int WTN, int KCH>
+__global__ __launch_bounds__(256, (WTM * WTN <= 8) ? 2 : 1) void xnor_gemm_mfma_fp4x_kernel(Fp4xParams p) {
+  constexpr int BM = 64 * WTM, BN = 64 * WTN, ROWS = BM + BN;
+  constexpr int RS = KCH / 2 + 16;        // bytes per LDS row
+  constexpr int PPR = KCH / 32;           // 16-byte pieces per row per chunk
+  constexpr int PPT = ROWS * PPR / 256;   // pieces per thread per chunk
+  static_assert(ROWS * PPR % 256 == 0, "staging must divide evenly");
+  static_assert(2 * ROWS * RS <= 65536, "LDS budget");
+  __shared__ __attribute__((aligned(16))) uint8_t sT[2][ROWS * RS];
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int mi = blockIdx.x % p.tilesM, ni = blockIdx.x / p.tilesM;
+  const int m0 = mi * BM, n0 = ni * BN;
+
+  // this thread's pieces of a chunk: tile row (A rows first, then B rows) and piece within the chunk
+  const uint8_t *gp[PPT];
+  bool gok[PPT];
+  int gq[PPT], soff[PPT];
+#pragma unroll
+  for (int t = 0; t < PPT; ++t) {
+    const int idx = t * 256 + tid;
+    const int row = idx / PPR, q = idx % PPR;
+    const bool isA = row < BM;
+    const int grow = isA ? m0 + row : n0 + (row - BM);
+    gok[t] = isA ? grow < p.M : grow < p.N;
+    gp[t] = (isA ? p.A + (int64_t)grow * p.lda : p.B + (int64_t)grow * p.ldb) + 16 * q;
+    gq[t] = q;
+    soff[t] = row * RS + 16 * q;
+  }
+  const int nchunks = (p.pieces + PPR - 1) / PPR;
+  // Chunk c + 2 is requested before chunk c is multiplied and written to LDS after chunk c + 1's
+  // multiplications have been issued: a chunk is only 2 * WTM * WTN matrix instructions per wave,
+  // far less than a memory round trip, so one chunk of distance leaves every chunk waiting for
+  // its loads.  Two register sets, used alternately (the loop body is written out for both).
+  v4i stage0[PPT], stage1[PPT];
+  auto stage_load = [&](int c, v4i(&st)[PPT]) {
+#pragma unroll
+    for (int t = 0; t < PPT; ++t) {
+      v4i v = {0, 0, 0, 0};  // rows past M / N and pieces past the row's end: 0.0, adds nothing
+      if (gok[t] && c * PPR + gq[t] < p.pieces) v = *reinterpret_cast<const v4i *>(gp[t] + (int64_t)c * (KCH / 2));
+      st[t] = v;
+    }
+  };
+  auto stage_store = [&](int buf, const v4i(&st)[PPT]) {
+#pragma unroll
+    for (int t = 0; t < PPT; ++t) *reinterpret_cast<v4i *>(&sT[buf][soff[t]]) = st[t];
+  };
+
+  v16f_f4 acc[WTM][WTN];
+#pragma unroll
+  for (int a = 0; a < WTM; ++a)
+#pragma unroll
+    for (int b = 0; b < WTN; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
+
+  // lane l: row l % 32 of a block, values 32 * (l / 32) .. + 31 of a 64-value step (16 bytes)
+  const int arow = (32 * WTM * wm + (lane & 31)) * RS + 16 * (lane >> 5);
+  const int brow = (BM + 32 * WTN * wn + (lane & 31)) * RS + 16 * (lane >> 5);
+  const int scale1 = (int)0x7F7F7F7Fu;  // E8M0 127 = 2^0 in every byte
+
+  auto multiply = [&](int buf) {
+    const uint8_t *T = sT[buf];
+#pragma unroll
+    for (int ks = 0; ks < KCH / 64; ++ks) {
+      v8i_f4 a[WTM], b[WTN];
+#pragma unroll
+      for (int mb = 0; mb < WTM; ++mb) {
+        const v4i t = *reinterpret_cast<const v4i *>(T + arow + mb * 32 * RS + ks * 32);
+        a[mb] = v8i_f4{t[0], t[1], t[2], t[3], 0, 0, 0, 0};
+      }
+#pragma unroll
+      for (int nb = 0; nb < WTN; ++nb) {
+        const v4i t = *reinterpret_cast<const v4i *>(T + brow + nb * 32 * RS + ks * 32);
+        b[nb] = v8i_f4{t[0], t[1], t[2], t[3], 0, 0, 0, 0};
+      }
+#pragma unroll
+      for (int mb = 0; mb < WTM; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < WTN; ++nb)
+          acc[mb][nb] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[mb], b[nb], acc[mb][nb], 4, 4, 0, scale1, 0,
+                                                                        scale1);
+    }
+  };
+
+  // chunk 0 -> LDS buffer 0; chunk 1 waits in register set 1
+  stage_load(0, stage0);
+  stage_store(0, stage0);
+  if (nchunks > 1) stage_load(1, stage1);
+  __syncthreads();
+  // Chunk c sits in LDS buffer c % 2 and chunk c + 1 in register set (c + 1) % 2.  The other
+  // LDS buffer was last read in chunk c - 1, before the previous barrier.
+  for (int c = 0; c < nchunks; c += 2) {
+    if (c + 2 < nchunks) stage_load(c + 2, stage0);
+    multiply(0);
+    if (c + 1 < nchunks) {
+      stage_store(1, stage1);
+      __syncthreads();
+      if (c + 3 < nchunks) stage_load(c + 3, stage1);
+      multiply(1);
+      if (c + 2 < nchunks) {
+        stage_store(0, stage0);
+        __syncthreads();
+      }
+    }
+  }
+
+  // D[i][j] of a 32x32 block: lane l holds column j = l % 32; register r holds row
+  // i = 8*(r/4) + 4*(l/32) + (r%4).
+#pragma unroll
+  for (int mb = 0; mb < WTM; ++mb)
+#pragma unroll
+    for (int nb = 0; nb < WTN; ++nb) {
+      const int n = n0 + 32 * WTN * wn + 32 * nb + (lane & 31);
+      if (n >= p.N) continue;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = m0 + 32 * WTM * wm + 32 * mb + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (m < p.M) __builtin_nontemporal_store((int)acc[mb][nb][r], p.C + (int64_t)m * p.ldc + n);
+      }
+    }
+}
+
+// Packed sign rows -> E2M1 rows: one thread per 64-bit word (32 bytes out).
+__global__ __launch_bounds__(256) void expand_fp4_kernel(const uint64_t *__restrict__ src, int64_t src_ld, int K, int Kw,
+                                                         uint8_t *__restrict__ dst, int64_t dst_ld, int64_t total) {
+  const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (g >= total) return;
+  const int64_t row = g / Kw;
+  const int cw = (int)(g - row * Kw);
+  const uint64_t word = src[row * src_ld + cw];
+  const int left = K - 64 * cw;  // values of this word that exist: 1..64 (or more)
+  const uint64_t vmask = left >= 64 ? ~0ull : ((1ull << left) - 1ull);
+  uint8_t *o = dst + row * dst_ld + 32 * (int64_t)cw;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint32_t bits = (uint32_t)(word >> (32 * h)), val = (uint32_t)(vmask >> (32 * h));
+    v4i v;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t y = spread8_to_nibbles((bits >> (8 * e)) & 0xFFu);  // bit 4i = value i is +1
+      const uint32_t m = spread8_to_nibbles((val >> (8 * e)) & 0xFFu);   // bit 4i = value i exists
+      // -1.0 is 0xA, +1.0 is 0x2: clear the sign bit where the value is +1; 0x0 where there is no value
+      v[e] = (int)((0xAAAAAAAAu ^ (y << 3)) & (m * 0xFu));
+    }
+    *reinterpret_cast<v4i *>(o + 16 * h) = v;
+  }
+}
+
+template <int WTM, int WTN, int KCH>
+static void launch_fp4x(const Fp4xParams &p0, int64_t M, int64_t N, hipStream_t s) {
+  Fp4xParams p = p0;
+  constexpr int BM = 64 * WTM, BN = 64 * WTN;
+  p.tilesM = (int)((M + BM - 1) / BM);
+  const int64_t blocks = (int64_t)p.tilesM * ((N + BN - 1) / BN);
+  hipLaunchKernelGGL((xnor_gemm_mfma_fp4x_kernel<WTM, WTN, KCH>), dim3((unsigned)blocks), dim3(256), 0, s, p);
+}
+
 static bnn_status mfma_ablation_common(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb, int32_t *C,
                                        int64_t ldc, int64_t M, int64_t N, int64_t K, void *stream, bool fp4) {
   if (M < 0 || N < 0 || K <= 0) return BNN_ERR_SHAPE;
@@ -303,6 +485,74 @@ using namespace bnn;
 extern "C" bnn_status bnn_xnor_gemm_mfma_fp4(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb, int32_t *C,
                                              int64_t ldc, int64_t M, int64_t N, int64_t K, void *stream) {
   return mfma_ablation_common(A, lda, B, ldb, C, ldc, M, N, K, stream, true);
+}
+
+extern "C" int64_t bnn_fp4_row_bytes(int64_t K) { return K <= 0 ? 0 : 32 * bnn_packed_words(K); }
+
+extern "C" bnn_status bnn_expand_fp4(const uint64_t *src, int64_t rows, int64_t K, int64_t src_ld, uint8_t *dst,
+                                     int64_t dst_ld_bytes, void *stream) {
+  if (rows < 0 || K <= 0) return BNN_ERR_SHAPE;
+  const int64_t Kw = bnn_packed_words(K);
+  if (src_ld < Kw || dst_ld_bytes < 32 * Kw || (dst_ld_bytes & 15)) return BNN_ERR_STRIDE;
+  if (rows == 0) return BNN_OK;
+  if (!src || !dst) return BNN_ERR_NULL;
+  if (!aligned16(src) || !aligned16(dst)) return BNN_ERR_ALIGN;
+  if (K > 0xffffffLL || rows > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+  const int64_t total = rows * Kw, blocks = (total + 255) / 256;
+  if (blocks > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+  hipStream_t s = (hipStream_t)stream;
+  {
+    ProfScope ps(KID_EXPAND_FP4, s);
+    hipLaunchKernelGGL(expand_fp4_kernel, dim3((unsigned)blocks), dim3(256), 0, s, src, src_ld, (int)K, (int)Kw, dst,
+                       dst_ld_bytes, total);
+  }
+  return launch_status();
+}
+
+// tile: -1 chosen here; 0 128 x 128; 1 256 x 128; 2 128 x 256
+static bnn_status fp4x_impl(const uint8_t *A4, int64_t lda_bytes, const uint8_t *B4, int64_t ldb_bytes, int32_t *C,
+                            int64_t ldc, int64_t M, int64_t N, int64_t K, int tile, void *stream) {
+  if (M < 0 || N < 0 || K <= 0) return BNN_ERR_SHAPE;
+  const int64_t rb = bnn_fp4_row_bytes(K);
+  if (lda_bytes < rb || ldb_bytes < rb || (lda_bytes & 15) || (ldb_bytes & 15) || ldc < N) return BNN_ERR_STRIDE;
+  if (tile < -1 || tile > 2) return BNN_ERR_SHAPE;
+  if (M == 0 || N == 0) return BNN_OK;
+  if (!A4 || !B4 || !C) return BNN_ERR_NULL;
+  if (!aligned16(A4) || !aligned16(B4) || !aligned16(C)) return BNN_ERR_ALIGN;
+  if (M > 0x7fffff00LL || N > 0x7fffff00LL || K > 0xffffffLL) return BNN_ERR_UNSUPPORTED;  // fp32 counts: exact below 2^24
+  if (((M + 127) / 128) * ((N + 127) / 128) > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
+  Fp4xParams p;
+  p.A = A4; p.B = B4; p.lda = lda_bytes; p.ldb = ldb_bytes; p.ldc = ldc; p.C = C;
+  p.M = (int)M; p.N = (int)N; p.pieces = (int)(rb / 16); p.tilesM = 0;
+  if (tile < 0) {
+    // the larger tile along the longer side when it still gives every compute unit two workgroups
+    // (measured: 256 x 200704 x 2304 100 us on 256 x 128 tiles against 111; 128 x 131072 x 1152
+    // 24.5 us on 128 x 256 against 28.4; 512 x 16384 x 4608 33 us on 128 x 128 against 39.5)
+    const int64_t two_per_cu = 2 * (int64_t)device_cu_count();
+    if (M <= 128) tile = (N + 255) / 256 >= two_per_cu ? 2 : 0;
+    else tile = ((M + 255) / 256) * ((N + 127) / 128) >= two_per_cu ? 1 : 0;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  {
+    ProfScope ps(KID_XNOR_GEMM_MFMA_FP4X, s);
+    if (tile == 0) launch_fp4x<2, 2, 128>(p, M, N, s);
+    else if (tile == 1) launch_fp4x<4, 2, 128>(p, M, N, s);
+    else launch_fp4x<2, 4, 128>(p, M, N, s);
+  }
+  return launch_status();
+}
+
+extern "C" bnn_status bnn_xnor_gemm_mfma_fp4_expanded(const uint8_t *A4, int64_t lda_bytes, const uint8_t *B4,
+                                                      int64_t ldb_bytes, int32_t *C, int64_t ldc, int64_t M, int64_t N,
+                                                      int64_t K, void *stream) {
+  return fp4x_impl(A4, lda_bytes, B4, ldb_bytes, C, ldc, M, N, K, -1, stream);
+}
+
+// Declared in bnn_testing.h.
+extern "C" bnn_status bnn_testing_xnor_gemm_mfma_fp4_expanded(const uint8_t *A4, int64_t lda_bytes, const uint8_t *B4,
+                                                              int64_t ldb_bytes, int32_t *C, int64_t ldc, int64_t M,
+                                                              int64_t N, int64_t K, int tile, void *stream) {
+  return fp4x_impl(A4, lda_bytes, B4, ldb_bytes, C, ldc, M, N, K, tile, stream);
 }
 
 extern "C" bnn_status bnn_xnor_gemm_mfma_i8(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb, int32_t *C,

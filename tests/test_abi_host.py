@@ -242,6 +242,27 @@ def test_ablation_and_control_errors(L):
         assert mf(None, 4, None, 4, None, 8, 0, 8, 200, None) == OK        # empty problem: nothing touched
     # the fp4 form counts in fp32: reductions of 2^24 bits and more are refused
     assert L.bnn_xnor_gemm_mfma_fp4(A16, 1 << 18, A16, 1 << 18, A16, 8, 8, 8, 1 << 24, None) == UNSUPPORTED
+    # operands kept expanded in memory: strides in bytes, multiples of 16
+    fx = L.bnn_xnor_gemm_mfma_fp4_expanded
+    assert L.bnn_fp4_row_bytes(1) == 32 and L.bnn_fp4_row_bytes(64) == 32 and L.bnn_fp4_row_bytes(65) == 64
+    assert L.bnn_fp4_row_bytes(0) == 0
+    assert fx(A16, 128, A16, 128, A16, 8, 8, 8, 0, None) == SHAPE
+    assert fx(A16, 96, A16, 128, A16, 8, 8, 8, 200, None) == STRIDE        # a row of 200 values takes 128 bytes
+    assert fx(A16, 136, A16, 128, A16, 8, 8, 8, 200, None) == STRIDE       # not a multiple of 16
+    assert fx(A16, 128, A16, 128, A16, 4, 8, 8, 200, None) == STRIDE       # ldc < N
+    assert fx(A16, 128, A16, 128, None, 8, 8, 8, 200, None) == NULL
+    assert fx(A16, 128, MIS, 128, A16, 8, 8, 8, 200, None) == ALIGN
+    assert fx(None, 128, None, 128, None, 8, 0, 8, 200, None) == OK
+    assert fx(A16, 1 << 23, A16, 1 << 23, A16, 8, 8, 8, 1 << 24, None) == UNSUPPORTED
+    assert L.bnn_testing_xnor_gemm_mfma_fp4_expanded(A16, 128, A16, 128, A16, 8, 8, 8, 200, 3, None) == SHAPE  # no such tile
+    ex = L.bnn_expand_fp4
+    assert ex(A16, 4, 0, 4, A16, 128, None) == SHAPE
+    assert ex(A16, 4, 200, 3, A16, 128, None) == STRIDE                    # source rows shorter than 4 words
+    assert ex(A16, 4, 200, 4, A16, 96, None) == STRIDE
+    assert ex(A16, 4, 200, 4, A16, 136, None) == STRIDE
+    assert ex(A16, 4, 200, 4, None, 128, None) == NULL
+    assert ex(MIS, 4, 200, 4, A16, 128, None) == ALIGN
+    assert ex(None, 0, 200, 4, None, 128, None) == OK
     cc = L.bnn_control_conv2d_f32
     assert cc(A16, A16, 2, 3, 8, 8, 4, 9, 9, 1, 1, 0, 0, A16, None) == SHAPE   # kernel larger than image
     assert cc(A16, A16, 2, 3, 8, 8, -1, 3, 3, 1, 1, 1, 1, A16, None) == SHAPE

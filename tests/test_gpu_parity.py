@@ -684,6 +684,54 @@ def test_mfma_ablation_equals_valu_path_at_cfg2():
     assert np.array_equal(host(B.bnn_xnor_gemm_mfma_fp4(Ap, Wp, inputs.CFG2.K)), b)
 
 
+def _e2m1_rows(x):
+    """Rows of +-1 values as 4-bit floating-point codes, written out from the format's definition:
+    +1.0 is 0x2, -1.0 is 0xA, value k in nibble k % 2 (low first) of byte k / 2, rows padded with
+    0.0 (0x0) to a multiple of 64 values."""
+    rows, K = x.shape
+    Kp = (K + 63) // 64 * 64
+    codes = np.zeros((rows, Kp), dtype=np.uint8)
+    codes[:, :K] = np.where(x >= 0, 0x2, 0xA)
+    return (codes[:, 0::2] | (codes[:, 1::2] << 4)).astype(np.uint8)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (37, 150, 300), (128, 128, 64), (130, 257, 1152), (64, 64, 256),
+                                   (200, 333, 2304 + 17), (5, 700, 63), (300, 3300, 200), (513, 1650, 127),
+                                   (256, 1000, 128), (260, 129, 192)])
+def test_mfma_fp4_expanded_ablation_matches_oracle(M, N, K):
+    """Operands kept in memory as E2M1 +-1 rows: the expansion pass against the format's definition,
+    the GEMM on every workgroup tile against the oracle."""
+    print(f"mfma fp4 expanded M={M} N={N} K={K}", flush=True)
+    rng = np.random.default_rng(M * 7919 + N * 31 + K + 5)
+    A = inputs.inject_specials(rng.standard_normal((M, K)).astype(np.float32), 1, frac=0.002)
+    Bm = inputs.inject_specials(rng.standard_normal((N, K)).astype(np.float32), 2, frac=0.002)
+    A4, B4 = B.bnn_expand_fp4(B.bnn_encode(dev(A)), K), B.bnn_expand_fp4(B.bnn_encode(dev(Bm)), K)
+    assert np.array_equal(host(A4), _e2m1_rows(A))
+    assert np.array_equal(host(B4), _e2m1_rows(Bm))
+    ref = oracle.gemm_pm1(A, Bm)
+    for tile in (None, 0, 1, 2):
+        assert np.array_equal(host(B.bnn_xnor_gemm_mfma_fp4_expanded(A4, B4, K, tile=tile)), ref), f"tile {tile}"
+
+
+def test_mfma_fp4_expanded_strided_operands_and_output():
+    """Leading dimensions larger than the rows: operands inside wider buffers, C inside a wider matrix."""
+    print("mfma fp4 expanded strided", flush=True)
+    M, N, K = 70, 200, 330
+    rng = np.random.default_rng(77)
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    Bm = rng.standard_normal((N, K)).astype(np.float32)
+    rb = 32 * ((K + 63) // 64)
+    A4w = torch.full((M, rb + 48), 0x77, dtype=torch.uint8, device="cuda")
+    B4w = torch.full((N, rb + 16), 0x77, dtype=torch.uint8, device="cuda")
+    B.bnn_expand_fp4(B.bnn_encode(dev(A)), K, out=A4w[:, :rb])
+    B.bnn_expand_fp4(B.bnn_encode(dev(Bm)), K, out=B4w[:, :rb])
+    assert np.array_equal(host(A4w[:, :rb]), _e2m1_rows(A)) and bool((A4w[:, rb:] == 0x77).all())
+    Cw = torch.full((M, N + 24), -7, dtype=torch.int32, device="cuda")
+    B.bnn_xnor_gemm_mfma_fp4_expanded(A4w[:, :rb], B4w[:, :rb], K, C=Cw[:, :N])
+    assert np.array_equal(host(Cw[:, :N]), oracle.gemm_pm1(A, Bm))
+    assert bool((Cw[:, N:] == -7).all())
+
+
 # ---------------------------------------------------------------- fp32 control group (section 4.4)
 @pytest.mark.parametrize("case", PACKED_CASES + [(1, 3, 5, 5, 130, 3, 3, 1, 1, 1, 1), (2, 40, 20, 20, 200, 3, 3, 2, 2, 0, 0)])
 def test_control_group_conv_equals_binarized_result(case):
