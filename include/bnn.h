@@ -42,7 +42,7 @@
  * ----------------------------------------------------------------------
  *  Every limit is checked on the host.  They follow from 32-bit indices inside the kernels:
  *   - GEMM entry points: M, K below 2^31, N at most 2^31 - 257; operand A at most 4 GiB (M * lda * 8 bytes).
- *     The MFMA ablations: K below 2^29 (int8), below 2^24 (fp4).
+ *     The MFMA ablations: K below 2^29 (int8), below 2^24 (both fp4 forms).
  *   - Convolutions: N*H*W below 2^31 pixels; N*C*H*W at most 2^33 values; N*OH*OW at most
  *     2^29 output pixels; N*OH*OW*bnn_conv_kwords() below 2^31 words; kH*kW at most 32767;
  *     the packed filter bank at most 4 GiB; D*N*OH*OW at most 2^34 outputs; the packed
