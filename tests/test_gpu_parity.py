@@ -800,6 +800,71 @@ def test_gemm_many_columns():
     assert np.array_equal(got, oracle.gemm_pm1(A, Bm))
 
 
+@pytest.mark.parametrize("N,C", [(255, 128), (510, 64)])
+def test_conv2d_packed_largest_images(N, C):
+    """Batches at the documented limit of N*C*H*W (2^33 values): 67 / 134 million pixels, a packed input of
+    1 GiB; C = 128 takes the table-driven gather, C = 64 (one word per pixel) the general one.  The batch
+    repeats three distinct images, so every image's result is known from the oracle's three."""
+    print(f"conv2d_packed largest images N={N} C={C}", flush=True)
+    H, W, D, st, pd = 512, 512, 8, (1, 1), (1, 1)
+    d = inputs.conv_inputs(inputs.ConvShape(3, C, H, W, D, 3, 3, 1, 1, 1, 1), seed=N)
+    x = inputs.inject_specials(d["x"], 6, frac=0.001)
+    ref = oracle.conv2d_pm1(x, d["w"], st, pd)
+    xp = _u64dev(oracle.pack_nhwc(x)).repeat(N // 3, 1, 1, 1)
+    wp = B.bnn_pack_conv_weight(dev(d["w"]))
+    # one image more is beyond the range: refused, nothing launched
+    with pytest.raises(B.BnnError):
+        B.bnn_conv2d_packed(torch.cat([xp, xp[:3]]), wp, C, D, 3, 3, st, pd, out="i32")
+    out = B.bnn_conv2d_packed(xp, wp, C, D, 3, 3, st, pd, out="i32")
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(N // 3, 3, D, H, W), dev(ref).expand(N // 3, 3, D, H, W))
+    del out
+    sc, bi = dev(d["scale"]), dev(d["bias"])
+    pref = oracle.pack_nhwc(oracle.scale_bias(oracle.maxpool2x2_i32(ref), d["scale"], d["bias"], "nchw"))
+    got = B.bnn_conv2d_packed(xp, wp, C, D, 3, 3, st, pd, pool=2, scale=sc, bias=bi, out="packed")
+    torch.cuda.synchronize()
+    assert torch.equal(got.view(N // 3, 3, H // 2, W // 2, 1), _u64dev(pref).expand(N // 3, 3, H // 2, W // 2, 1))
+    del xp, got
+    torch.cuda.empty_cache()
+    if C == 128:
+        # the same batch as fp32 NCHW (34 GB) through bnn_conv2d: its encode, then the same GEMM
+        xf = dev(x).repeat(N // 3, 1, 1, 1)
+        oi, _ = B.bnn_conv2d(xf, wp, D, 3, 3, st, pd)
+        torch.cuda.synchronize()
+        assert torch.equal(oi.view(N // 3, 3, D, H, W), dev(ref).expand(N // 3, 3, D, H, W))
+        del xf, oi
+        torch.cuda.empty_cache()
+
+
+def _pm1_rows(packed, K):
+    """Packed rows (uint64 words, element k in bit k % 64 of word k / 64, bit 1 = +1) as +-1 floats."""
+    bits = np.unpackbits(np.ascontiguousarray(packed).view(np.uint8), axis=-1, bitorder="little")[:, :K]
+    return np.where(bits == 1, 1.0, -1.0).astype(np.float32)
+
+
+@pytest.mark.parametrize("N,K", [((1 << 31) - 257, 64), ((1 << 31) - 260, 128)])
+def test_gemm_maximum_column_count(N, K):
+    """The largest column count the header allows (2^31 - 257; the second case is the largest multiple of 4,
+    which the short-row kernel takes): 17 / 34 GB of packed rows, 17 GB of output, checked on the first and
+    last columns and on a random sample, against the oracle."""
+    print(f"gemm max columns N={N} K={K}", flush=True)
+    M, Kw = 2, K // 64
+    g = torch.Generator(device="cuda").manual_seed(191104477)
+    Bp = torch.randint(-2**63, 2**63 - 1, (N, Kw), dtype=torch.int64, device="cuda", generator=g)
+    Ap = torch.randint(-2**63, 2**63 - 1, (M, Kw), dtype=torch.int64, device="cuda", generator=g)
+    C = B.bnn_xnor_gemm(Ap, Bp, K)
+    rng = np.random.default_rng(3)
+    idx = np.unique(np.concatenate([np.arange(0, 1024), np.arange(N - 1024, N),
+                                    rng.integers(0, N, size=200_000)])).astype(np.int64)
+    it = torch.from_numpy(idx).cuda()
+    got = host(C[:, it])
+    rows = host(Bp[it]).view(np.uint64)
+    ref = oracle.gemm_pm1(_pm1_rows(host(Ap).view(np.uint64), K), _pm1_rows(rows, K))
+    assert np.array_equal(got, ref)
+    del Bp, C
+    torch.cuda.empty_cache()
+
+
 def test_fused_stack_split_over_two_streams_matches_oracle():
     print("split batch over two streams", flush=True)
     from paper_1911_04477_amd.stack import SplitBatch
