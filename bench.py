@@ -12,9 +12,11 @@ line; the other configurations, the streaming kernels and the MFMA ablation ride
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4|cfg2|cfg3|cfg5a|cfg5b]
 
-The defaults (200 warm-up + 1000 timed steps, about half a second of GPU time) matter: the
-GPU reaches its sustained clocks only after some tens of milliseconds of continuous work, and
-a 20-step run of this 0.33 ms step reads 25 % slower than the sustained rate.
+The defaults (200 warm-up + 1000 timed steps, about a third of a second of GPU time) matter: a
+GPU that was idle reaches its sustained clocks only after about 35 ms of continuous work (the
+step falls from 0.303 to 0.277 ms over the first 80 steps and stays there), so a run of 5 + 20
+steps of this 0.28 ms step, 7 ms in all, reads 9 % slower than the sustained rate.  Such a run
+prints the 200 + 1000 figure beside its own, as `sustained`.
 """
 from __future__ import annotations
 
