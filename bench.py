@@ -461,6 +461,27 @@ def mfma_ablation():
                      "expand_B_us": round(te / 200 * 1e6, 1),
                      "expand_B_GBs": round((Bm.numel() * 8 + B4.numel()) / (te / 200) / 1e9, 1)}
         del A, Bm, C, C2, C3, C4, A4, B4
+    # the same ablation as a convolution: patches gathered inside the GEMM from a 4-bit NHWC image,
+    # beside the VALU convolution from the 1-bit image (both int32 NCHW out, images already in their format)
+    for name, (N, Cc, H, W, D) in (("cfg5a_conv_64x256x56x56_to_256", (64, 256, 56, 56, 256)),
+                                   ("cfg3_conv_128x128x32x32_to_128", (128, 128, 32, 32, 128))):
+        Cw = Cc // 64
+        xp = torch.randint(-2**62, 2**62, (N, H, W, Cw), dtype=torch.int64, device=dev)
+        wp = torch.randint(-2**62, 2**62, (D, 9 * Cw), dtype=torch.int64, device=dev)
+        x4 = B.bnn_expand_fp4(xp.view(N * H * W, Cw), Cc).view(N, H, W, Cc // 2)
+        w4 = B.bnn_expand_fp4(wp, 9 * Cc)
+        o1 = torch.empty((N, D, H, W), dtype=torch.int32, device=dev)
+        o2 = torch.empty((N, D, H, W), dtype=torch.int32, device=dev)
+        tv, _ = time_steps(lambda: B.bnn_conv2d_packed(xp, wp, Cc, D, 3, 3, (1, 1), (1, 1), out="i32", out_buf=o1), 200, 100)
+        tx, _ = time_steps(lambda: B.bnn_conv2d_mfma_fp4_expanded(x4, w4, Cc, D, 3, 3, (1, 1), (1, 1), out=o2), 200, 100)
+        te = graph_time(lambda: B.bnn_expand_fp4(xp.view(N * H * W, Cw), Cc, out=x4.view(N * H * W, Cc // 2)))
+        bops = 2.0 * N * H * W * D * 9 * Cc
+        out[name] = {"valu_TBOPS": round(bops / (tv / 200) / 1e12, 1),
+                     "mfma_fp4_expanded_TBOPS": round(bops / (tx / 200) / 1e12, 1),
+                     "bit_identical": bool((o1 == o2).all().item()),
+                     "mfma_fp4_expanded_frac_of_fp4_dense_peak": round(bops / (tx / 200) / 10.1e15, 4),
+                     "expand_image_us": round(te * 1e6, 1)}
+        del xp, wp, x4, w4, o1, o2
     return out
 
 

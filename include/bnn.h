@@ -319,6 +319,21 @@ BNN_API bnn_status bnn_xnor_gemm_mfma_fp4_expanded(const uint8_t *A4, int64_t ld
                                                    int64_t ldb_bytes, int32_t *C, int64_t ldc, int64_t M,
                                                    int64_t N, int64_t K, void *stream);
 
+/*
+ * bnn_conv2d_mfma_fp4_expanded -- the same ABLATION as a convolution (sections 2.1 and 3.2): the
+ * patches are gathered inside the GEMM from a 4-bit NHWC image, so the patch matrix (kH*kW times
+ * the image) never exists.  out[n, d, oh, ow] as bnn_conv2d's int32 output, taps outside the image
+ * counting as +1.
+ *   x4 [N, H, W, C / 2 bytes]: bnn_expand_fp4 of the packed NHWC image taken as N*H*W rows of C
+ *     values; w4 [D, kH*kW*C / 2 bytes]: bnn_expand_fp4 of bnn_pack_conv_weight's rows
+ *     (K = kH*kW*C); out_i32 [N, D, OH, OW] (device, written).  All 16-byte aligned.
+ *   C must be a multiple of 64 (BNN_ERR_UNSUPPORTED otherwise), C*kH*kW below 2^24.
+ * Errors as bnn_conv2d.  Not used by any other entry point.
+ */
+BNN_API bnn_status bnn_conv2d_mfma_fp4_expanded(const uint8_t *x4, const uint8_t *w4, int N, int C, int H, int W,
+                                                int D, int kH, int kW, int sH, int sW, int pH, int pW,
+                                                int32_t *out_i32, void *stream);
+
 /* ---- control group --------------------------------------------------------------------- */
 
 /*

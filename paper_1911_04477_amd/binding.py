@@ -36,6 +36,7 @@ SIGNATURES = {
     "bnn_fp4_row_bytes": (_i64, [_i64]),
     "bnn_expand_fp4": (_i32, [_p, _i64, _i64, _i64, _p, _i64, _p]),
     "bnn_xnor_gemm_mfma_fp4_expanded": (_i32, [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _p]),
+    "bnn_conv2d_mfma_fp4_expanded": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p]),
     "bnn_control_conv2d_f32": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p]),
     "bnn_xnor_gemm_epilogue": (_i32, [_p, _i64, _p, _i64, _i64, _i64, _i64, _p, _i64, _p, _i64, _p, _p, _i32, _p]),
     "bnn_conv2d": (_i32, [_p, _p] + [_i32] * 11 + [_p, _p, _p, _p, _p, _sz, _p]),
@@ -255,6 +256,21 @@ def bnn_xnor_gemm_mfma_fp4_expanded(A4: torch.Tensor, B4: torch.Tensor, K: int, 
         _check(lib().bnn_testing_xnor_gemm_mfma_fp4_expanded(_ptr(A4), lda, _ptr(B4), ldb, _ptr(C), ldc, M, N, K, tile,
                                                              _stream()), "bnn_testing_xnor_gemm_mfma_fp4_expanded")
     return C
+
+
+def bnn_conv2d_mfma_fp4_expanded(x4: torch.Tensor, w4: torch.Tensor, C: int, D: int, kH: int, kW: int, stride=(1, 1),
+                                 pad=(0, 0), out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Ablation: x4 [N, H, W, C/2] uint8 (E2M1 codes), w4 [D, kH*kW*C/2] uint8 -> int32 NCHW."""
+    _dev(x4, torch.uint8, "x4")
+    _dev(w4, torch.uint8, "w4")
+    assert x4.dim() == 4 and x4.is_contiguous() and w4.is_contiguous()
+    N, H, W, _ = x4.shape
+    OH, OW = conv_out_dim(H, kH, stride[0], pad[0]), conv_out_dim(W, kW, stride[1], pad[1])
+    if out is None:
+        out = torch.empty((N, D, OH, OW), dtype=torch.int32, device=x4.device)
+    _check(lib().bnn_conv2d_mfma_fp4_expanded(_ptr(x4), _ptr(w4), N, C, H, W, D, kH, kW, stride[0], stride[1], pad[0],
+                                              pad[1], _ptr(out), _stream()), "bnn_conv2d_mfma_fp4_expanded")
+    return out
 
 
 def bnn_control_conv2d_f32(x: torch.Tensor, w: torch.Tensor, stride=(1, 1), pad=(0, 0),

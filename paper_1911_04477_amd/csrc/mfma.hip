@@ -289,9 +289,18 @@ struct Fp4xParams {
   int M, N;
   int pieces;  // 16-byte pieces per row: 2 * ceil(K / 64)
   int tilesM;
+  // convolution form (CONV = 1): B is a 4-bit NHWC image [Nimg, H, W, C / 2 bytes], column n is
+  // output pixel n, piece j of its row is channels 32 * (j % ppt) .. + 31 of tap j / ppt, and the
+  // output is NCHW (row m = output channel)
+  int H, W, OH, OW, kW, sH, sW, pH, pW;
+  int ppt;               // 16-byte pieces per tap: C / 32
+  int64_t pix_bytes;     // C / 2
+  int64_t img_stride;    // D * OH * OW outputs per image
+  uint32_t OHW;
+  FastDiv divPpt, divKW, divOW, divOH, divOHW;
 };
 
-template <int WTM, int WTN, int KCH>
+template <int WTM, int WTN, int KCH, int CONV>
 __global__ __launch_bounds__(256, (WTM * WTN <= 8) ? 2 : 1) void xnor_gemm_mfma_fp4x_kernel(Fp4xParams p) {
   constexpr int BM = 64 * WTM, BN = 64 * WTN, ROWS = BM + BN;
   constexpr int RS = KCH / 2 + 16;        // bytes per LDS row
@@ -311,6 +320,9 @@ __global__ __launch_bounds__(256, (WTM * WTN <= 8) ? 2 : 1) void xnor_gemm_mfma_
   const uint8_t *gp[PPT];
   bool gok[PPT];
   int gq[PPT], soff[PPT];
+  // convolution form, B rows: the pixel under tap (0, 0) of this thread's output pixel
+  bool gconv[PPT];
+  int gih0[PPT], giw0[PPT];
 #pragma unroll
   for (int t = 0; t < PPT; ++t) {
     const int idx = t * 256 + tid;
@@ -318,9 +330,22 @@ __global__ __launch_bounds__(256, (WTM * WTN <= 8) ? 2 : 1) void xnor_gemm_mfma_
     const bool isA = row < BM;
     const int grow = isA ? m0 + row : n0 + (row - BM);
     gok[t] = isA ? grow < p.M : grow < p.N;
-    gp[t] = (isA ? p.A + (int64_t)grow * p.lda : p.B + (int64_t)grow * p.ldb) + 16 * q;
     gq[t] = q;
     soff[t] = row * RS + 16 * q;
+    gconv[t] = CONV && !isA;
+    gih0[t] = giw0[t] = 0;
+    if (CONV && !isA) {
+      const uint32_t n = gok[t] ? (uint32_t)grow : 0u;
+      const uint32_t tq = fdiv(n, p.divOW);
+      const uint32_t ow = n - tq * (uint32_t)p.OW;
+      const uint32_t img = fdiv(tq, p.divOH);
+      const uint32_t oh = tq - img * (uint32_t)p.OH;
+      gih0[t] = (int)oh * p.sH - p.pH;
+      giw0[t] = (int)ow * p.sW - p.pW;
+      gp[t] = p.B + (int64_t)img * p.H * p.W * p.pix_bytes;  // the pixel's image
+    } else {
+      gp[t] = (isA ? p.A + (int64_t)grow * p.lda : p.B + (int64_t)grow * p.ldb) + 16 * q;
+    }
   }
   const int nchunks = (p.pieces + PPR - 1) / PPR;
   // Chunk c + 2 is requested before chunk c is multiplied and written to LDS after chunk c + 1's
@@ -332,7 +357,21 @@ __global__ __launch_bounds__(256, (WTM * WTN <= 8) ? 2 : 1) void xnor_gemm_mfma_
 #pragma unroll
     for (int t = 0; t < PPT; ++t) {
       v4i v = {0, 0, 0, 0};  // rows past M / N and pieces past the row's end: 0.0, adds nothing
-      if (gok[t] && c * PPR + gq[t] < p.pieces) v = *reinterpret_cast<const v4i *>(gp[t] + (int64_t)c * (KCH / 2));
+      const int j = c * PPR + gq[t];
+      if (gok[t] && j < p.pieces) {
+        if (CONV && gconv[t]) {
+          const uint32_t tap = fdiv((uint32_t)j, p.divPpt);
+          const uint32_t cq = (uint32_t)j - tap * (uint32_t)p.ppt;
+          const uint32_t kh = fdiv(tap, p.divKW);
+          const int ih = gih0[t] + (int)kh, iw = giw0[t] + (int)(tap - kh * (uint32_t)p.kW);
+          if (ih >= 0 && ih < p.H && iw >= 0 && iw < p.W)
+            v = *reinterpret_cast<const v4i *>(gp[t] + ((int64_t)ih * p.W + iw) * p.pix_bytes + 16 * (int64_t)cq);
+          else
+            v = v4i{0x22222222, 0x22222222, 0x22222222, 0x22222222};  // taps outside the image: +1.0
+        } else {
+          v = *reinterpret_cast<const v4i *>(gp[t] + (int64_t)c * (KCH / 2));
+        }
+      }
       st[t] = v;
     }
   };
@@ -408,10 +447,15 @@ __global__ __launch_bounds__(256, (WTM * WTN <= 8) ? 2 : 1) void xnor_gemm_mfma_
     for (int nb = 0; nb < WTN; ++nb) {
       const int n = n0 + 32 * WTN * wn + 32 * nb + (lane & 31);
       if (n >= p.N) continue;
+      int64_t col = n;  // row-major C; NCHW: image * (D * OH * OW) + pixel, rows OH * OW apart
+      if (CONV) {
+        const uint32_t img = fdiv((uint32_t)n, p.divOHW);
+        col = (int64_t)img * p.img_stride + ((uint32_t)n - img * p.OHW);
+      }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int m = m0 + 32 * WTM * wm + 32 * mb + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (m < p.M) __builtin_nontemporal_store((int)acc[mb][nb][r], p.C + (int64_t)m * p.ldc + n);
+        if (m < p.M) __builtin_nontemporal_store((int)acc[mb][nb][r], p.C + (int64_t)m * p.ldc + col);
       }
     }
 }
@@ -442,13 +486,13 @@ __global__ __launch_bounds__(256) void expand_fp4_kernel(const uint64_t *__restr
   }
 }
 
-template <int WTM, int WTN, int KCH>
+template <int WTM, int WTN, int KCH, int CONV>
 static void launch_fp4x(const Fp4xParams &p0, int64_t M, int64_t N, hipStream_t s) {
   Fp4xParams p = p0;
   constexpr int BM = 64 * WTM, BN = 64 * WTN;
   p.tilesM = (int)((M + BM - 1) / BM);
   const int64_t blocks = (int64_t)p.tilesM * ((N + BN - 1) / BN);
-  hipLaunchKernelGGL((xnor_gemm_mfma_fp4x_kernel<WTM, WTN, KCH>), dim3((unsigned)blocks), dim3(256), 0, s, p);
+  hipLaunchKernelGGL((xnor_gemm_mfma_fp4x_kernel<WTM, WTN, KCH, CONV>), dim3((unsigned)blocks), dim3(256), 0, s, p);
 }
 
 static bnn_status mfma_ablation_common(const uint64_t *A, int64_t lda, const uint64_t *B, int64_t ldb, int32_t *C,
@@ -521,23 +565,23 @@ static bnn_status fp4x_impl(const uint8_t *A4, int64_t lda_bytes, const uint8_t 
   if (!aligned16(A4) || !aligned16(B4) || !aligned16(C)) return BNN_ERR_ALIGN;
   if (M > 0x7fffff00LL || N > 0x7fffff00LL || K > 0xffffffLL) return BNN_ERR_UNSUPPORTED;  // fp32 counts: exact below 2^24
   if (((M + 127) / 128) * ((N + 127) / 128) > 0x7fffffffLL) return BNN_ERR_UNSUPPORTED;
-  Fp4xParams p;
+  Fp4xParams p = {};
   p.A = A4; p.B = B4; p.lda = lda_bytes; p.ldb = ldb_bytes; p.ldc = ldc; p.C = C;
   p.M = (int)M; p.N = (int)N; p.pieces = (int)(rb / 16); p.tilesM = 0;
-  if (tile < 0) {
-    // the larger tile along the longer side when it still gives every compute unit two workgroups
-    // (measured: 256 x 200704 x 2304 100 us on 256 x 128 tiles against 111; 128 x 131072 x 1152
-    // 24.5 us on 128 x 256 against 28.4; 512 x 16384 x 4608 33 us on 128 x 128 against 39.5)
-    const int64_t two_per_cu = 2 * (int64_t)device_cu_count();
-    if (M <= 128) tile = (N + 255) / 256 >= two_per_cu ? 2 : 0;
-    else tile = ((M + 255) / 256) * ((N + 127) / 128) >= two_per_cu ? 1 : 0;
-  }
   hipStream_t s = (hipStream_t)stream;
   {
     ProfScope ps(KID_XNOR_GEMM_MFMA_FP4X, s);
-    if (tile == 0) launch_fp4x<2, 2, 128>(p, M, N, s);
-    else if (tile == 1) launch_fp4x<4, 2, 128>(p, M, N, s);
-    else launch_fp4x<2, 4, 128>(p, M, N, s);
+    if (tile < 0) {
+      // the larger tile along the longer side when it still gives every compute unit two workgroups
+      // (measured: 256 x 200704 x 2304 100 us on 256 x 128 tiles against 111; 128 x 131072 x 1152
+      // 24.5 us on 128 x 256 against 28.4; 512 x 16384 x 4608 33 us on 128 x 128 against 39.5)
+      const int64_t two_per_cu = 2 * (int64_t)device_cu_count();
+      if (M <= 128) tile = (N + 255) / 256 >= two_per_cu ? 2 : 0;
+      else tile = ((M + 255) / 256) * ((N + 127) / 128) >= two_per_cu ? 1 : 0;
+    }
+    if (tile == 0) launch_fp4x<2, 2, 128, 0>(p, M, N, s);
+    else if (tile == 1) launch_fp4x<4, 2, 128, 0>(p, M, N, s);
+    else launch_fp4x<2, 4, 128, 0>(p, M, N, s);
   }
   return launch_status();
 }
@@ -546,6 +590,44 @@ extern "C" bnn_status bnn_xnor_gemm_mfma_fp4_expanded(const uint8_t *A4, int64_t
                                                       int64_t ldb_bytes, int32_t *C, int64_t ldc, int64_t M, int64_t N,
                                                       int64_t K, void *stream) {
   return fp4x_impl(A4, lda_bytes, B4, ldb_bytes, C, ldc, M, N, K, -1, stream);
+}
+
+extern "C" bnn_status bnn_conv2d_mfma_fp4_expanded(const uint8_t *x4, const uint8_t *w4, int N, int C, int H, int W,
+                                                   int D, int kH, int kW, int sH, int sW, int pH, int pW,
+                                                   int32_t *out_i32, void *stream) {
+  bnn_status st = check_conv_geometry(N, C, H, W, kH, kW, sH, sW, pH, pW);
+  if (st != BNN_OK) return st;
+  if (D < 0) return BNN_ERR_SHAPE;
+  if (C % 64 != 0) return BNN_ERR_UNSUPPORTED;  // whole words per pixel: no pad channels inside a tap
+  if (N == 0 || D == 0) return BNN_OK;
+  if (!x4 || !w4 || !out_i32) return BNN_ERR_NULL;
+  if (!aligned16(x4) || !aligned16(w4) || !aligned16(out_i32)) return BNN_ERR_ALIGN;
+  const int64_t OH = bnn_conv_out_dim(H, kH, sH, pH), OW = bnn_conv_out_dim(W, kW, sW, pW);
+  const int64_t P = (int64_t)N * OH * OW, K = (int64_t)C * kH * kW;
+  if (K > 0xffffffLL || P > 0x7fffff00LL || D > 0x7fffff00LL || (int64_t)D * P > 0x7fffffffLL * 8 ||
+      ((D + 127) / 128) * ((P + 127) / 128) > 0x7fffffffLL)
+    return BNN_ERR_UNSUPPORTED;
+  Fp4xParams p = {};
+  p.A = w4; p.B = x4; p.lda = K / 2; p.ldb = 0; p.ldc = OH * OW; p.C = out_i32;
+  p.M = D; p.N = (int)P; p.pieces = (int)(K / 32); p.tilesM = 0;
+  p.H = H; p.W = W; p.OH = (int)OH; p.OW = (int)OW; p.kW = kW; p.sH = sH; p.sW = sW; p.pH = pH; p.pW = pW;
+  p.ppt = C / 32;
+  p.pix_bytes = C / 2;
+  p.img_stride = (int64_t)D * OH * OW;
+  p.OHW = (uint32_t)(OH * OW);
+  p.divPpt = FastDiv((uint32_t)p.ppt);
+  p.divKW = FastDiv((uint32_t)kW);
+  p.divOW = FastDiv((uint32_t)OW);
+  p.divOH = FastDiv((uint32_t)OH);
+  p.divOHW = FastDiv(p.OHW);
+  hipStream_t s = (hipStream_t)stream;
+  {
+    ProfScope ps(KID_XNOR_GEMM_MFMA_FP4X, s);
+    // 128 x 128 tiles: with the gather's addressing the larger ones no longer fit the register file
+    // (measured with spills: cfg 5a 142 / 179 us against 108)
+    launch_fp4x<2, 2, 128, 1>(p, D, P, s);
+  }
+  return launch_status();
 }
 
 // Declared in bnn_testing.h.

@@ -263,6 +263,12 @@ def test_ablation_and_control_errors(L):
     assert ex(A16, 4, 200, 4, None, 128, None) == NULL
     assert ex(MIS, 4, 200, 4, A16, 128, None) == ALIGN
     assert ex(None, 0, 200, 4, None, 128, None) == OK
+    cx = L.bnn_conv2d_mfma_fp4_expanded
+    assert cx(A16, A16, 2, 64, 8, 8, 4, 9, 9, 1, 1, 0, 0, A16, None) == SHAPE      # kernel larger than image
+    assert cx(A16, A16, 2, 100, 8, 8, 4, 3, 3, 1, 1, 1, 1, A16, None) == UNSUPPORTED  # C not a multiple of 64
+    assert cx(A16, None, 2, 64, 8, 8, 4, 3, 3, 1, 1, 1, 1, A16, None) == NULL
+    assert cx(A16, A16, 2, 64, 8, 8, 4, 3, 3, 1, 1, 1, 1, MIS, None) == ALIGN
+    assert cx(None, None, 0, 64, 8, 8, 4, 3, 3, 1, 1, 1, 1, None, None) == OK       # empty batch
     cc = L.bnn_control_conv2d_f32
     assert cc(A16, A16, 2, 3, 8, 8, 4, 9, 9, 1, 1, 0, 0, A16, None) == SHAPE   # kernel larger than image
     assert cc(A16, A16, 2, 3, 8, 8, -1, 3, 3, 1, 1, 1, 1, A16, None) == SHAPE

@@ -732,6 +732,24 @@ def test_mfma_fp4_expanded_strided_operands_and_output():
     assert bool((Cw[:, N:] == -7).all())
 
 
+@pytest.mark.parametrize("case", [(2, 64, 9, 7, 40, 3, 3, 1, 1, 1, 1), (3, 128, 12, 12, 130, 3, 3, 1, 1, 1, 1),
+                                  (2, 192, 11, 10, 70, 3, 3, 2, 2, 1, 1), (1, 64, 8, 8, 300, 1, 1, 1, 1, 0, 0),
+                                  (2, 128, 9, 9, 33, 5, 3, 1, 2, 2, 0), (2, 256, 14, 14, 256, 3, 3, 1, 1, 1, 1),
+                                  (5, 64, 6, 6, 17, 2, 2, 1, 1, 1, 1)])
+def test_conv2d_mfma_fp4_expanded_matches_oracle(case):
+    """The matrix-core ablation as a convolution: patches gathered from the 4-bit NHWC image."""
+    print(f"conv2d mfma fp4 expanded case={case}", flush=True)
+    N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
+    d = inputs.conv_inputs(inputs.ConvShape(*case), seed=sum(case) + 23)
+    x = inputs.inject_specials(d["x"], 7, frac=0.01)
+    Cw = C // 64
+    x4 = B.bnn_expand_fp4(_u64dev(oracle.pack_nhwc(x)).view(N * H * W, Cw), C).view(N, H, W, C // 2)
+    assert np.array_equal(host(x4).reshape(N * H * W, C // 2), _e2m1_rows(x.transpose(0, 2, 3, 1).reshape(N * H * W, C)))
+    w4 = B.bnn_expand_fp4(B.bnn_pack_conv_weight(dev(d["w"])), C * kH * kW)
+    got = host(B.bnn_conv2d_mfma_fp4_expanded(x4, w4, C, D, kH, kW, (sH, sW), (pH, pW)))
+    assert np.array_equal(got, oracle.conv2d_pm1(x, d["w"], (sH, sW), (pH, pW)))
+
+
 # ---------------------------------------------------------------- fp32 control group (section 4.4)
 @pytest.mark.parametrize("case", PACKED_CASES + [(1, 3, 5, 5, 130, 3, 3, 1, 1, 1, 1), (2, 40, 20, 20, 200, 3, 3, 2, 2, 0, 0)])
 def test_control_group_conv_equals_binarized_result(case):
