@@ -107,6 +107,8 @@ struct GemmParams {
   int prio_from;       // workgroups with id >= prio_from lower their wave priority as they advance through K
   int n_cu;            // compute units of the device (host only: launch heuristics)
   int nt_store;        // int32 / fp32 tile stores are line-aligned: use non-temporal stores
+  int colperm;         // 256-column tiles, int32 / fp32 output: LDS row 64 * j + l holds tile column 4 * l + j,
+                       // so a lane's four columns are consecutive and go out as one 16-byte store per row
   ConvGeom g;          // implicit B only
   uint64_t *outp;      // packed-sign output [pixels, cw_out] (packed epilogue only)
   int cw_out;

@@ -30,7 +30,9 @@
 //     long-lived SGPRs (row offsets are recomputed by scalar adds per chunk), because the
 //     kernel is VALU-bound and SGPR spills are VALU instructions (v_readlane);
 //   * the store does K - 2*acc and then either writes int32 / fma(scale, acc, bias) fp32
-//     (row-major or scattered to NCHW, 256 contiguous bytes per wave store), or -- the
+//     (row-major or scattered to NCHW; 256 contiguous bytes per wave store, or, on the
+//     256-column tiles when N and the strides are multiples of 4, 1 KB: the tile's columns are
+//     then dealt to the LDS rows so that a lane's four columns are consecutive), or -- the
 //     binarizing epilogue -- takes the 2x2 max (optional), applies the fma, keeps only the
 //     sign and writes packed NHWC words for the next layer (32x fewer output bytes).
 // Workgroup ids are remapped so that tiles sharing a B tile run on the same XCD
@@ -177,6 +179,79 @@ __device__ __forceinline__ void store_tile(const int (&acc)[TM][TN], int m0, int
   }
 }
 
+// The same store for a column-permuted tile (GemmParams::colperm): the lane's four accumulators of a
+// row are four consecutive columns, first column nfirst (a multiple of 4), stored with one 16-byte
+// store per row.  The host sets colperm only where N, the leading dimensions and the columns per
+// image are multiples of 4, so the four columns are all inside or all outside the matrix, lie in one
+// image and start on a 16-byte boundary.
+__device__ __forceinline__ void store_tile_x4(const int (&acc)[TM][4], int m0, int nfirst) {
+  using i32x4 = int __attribute__((ext_vector_type(4)));
+  using f32x4 = float __attribute__((ext_vector_type(4)));
+  const GemmParams BNN_CONST_AS *kp = (const GemmParams BNN_CONST_AS *)__builtin_amdgcn_kernarg_segment_ptr();
+  asm volatile("" : "+s"(kp));
+  const int M = kp->M, N = kp->N, Kformula = kp->Kformula;
+  if (nfirst >= N) return;
+  const float *const scale = kp->scale, *const bias = kp->bias;
+  const int axis = kp->axis;
+  int32_t *const Cp = kp->C;
+  float *const Yp = kp->Y;
+  const int64_t ldc = kp->ldc, ldy = kp->ldy, img_stride = kp->img_stride;
+  const uint32_t OHW = kp->OHW;
+  const bool nt = kp->nt_store != 0;
+  FastDiv divOHW;
+  divOHW.d = kp->divOHW.d; divOHW.mul = kp->divOHW.mul; divOHW.shift = kp->divOHW.shift;
+  typedef const float BNN_CONST_AS *cf32_ptr;
+  const cf32_ptr cscale = (cf32_ptr)(uintptr_t)scale, cbias = (cf32_ptr)(uintptr_t)bias;
+  float scr[TM], bir[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    scr[i] = 1.0f;
+    bir[i] = 0.0f;
+  }
+  if (Yp && axis == BNN_CH_ROW) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int mi = min(m0 + i, M - 1);
+      scr[i] = cscale[mi];
+      bir[i] = cbias[mi];
+    }
+  }
+  f32x4 csc = {1.f, 1.f, 1.f, 1.f}, cbi = {0.f, 0.f, 0.f, 0.f};
+  if (Yp && axis == BNN_CH_COL) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {  // scale / bias carry no alignment requirement
+      csc[j] = scale[nfirst + j];
+      cbi[j] = bias[nfirst + j];
+    }
+  }
+  const uint32_t img = fdiv((uint32_t)nfirst, divOHW);
+  const uint32_t pix = (uint32_t)nfirst - img * OHW;
+  int32_t *cp = Cp ? Cp + ((int64_t)img * img_stride + pix + (int64_t)m0 * ldc) : nullptr;
+  float *yp = Yp ? Yp + ((int64_t)img * img_stride + pix + (int64_t)m0 * ldy) : nullptr;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    if (m0 + i < M) {
+      i32x4 v;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) v[j] = Kformula - 2 * acc[i][j];
+      if (cp) {
+        if (nt) __builtin_nontemporal_store(v, reinterpret_cast<i32x4 *>(cp));
+        else *reinterpret_cast<i32x4 *>(cp) = v;
+      }
+      if (yp) {
+        f32x4 y;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          y[j] = axis == BNN_CH_ROW ? fmaf(scr[i], (float)v[j], bir[i]) : fmaf(csc[j], (float)v[j], cbi[j]);
+        if (nt) __builtin_nontemporal_store(y, reinterpret_cast<f32x4 *>(yp));
+        else *reinterpret_cast<f32x4 *>(yp) = y;
+      }
+    }
+    if (cp) cp += ldc;
+    if (yp) yp += ldy;
+  }
+}
+
 template <int TN, int WM, int WN, int MINW, int BMODE, int EMODE, int YIELD>
 __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParams p) {
   using Cfg = GemmCfg<TN, WM, WN>;
@@ -204,6 +279,10 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   const int ni = (int)(tile / (uint32_t)p.tilesM);
   const int m0 = mi * Cfg::BM + wm * TM;
   const int n0 = ni * Cfg::BN;
+  // Tile column held by LDS row `row` of the B tile: the row itself, or (column-permuted tiles, see
+  // GemmParams::colperm) 4 * (row % 64) + row / 64.
+  const bool colperm = EMODE == 0 && TN == 4 && WN == 1 && p.colperm != 0;
+  auto tile_col = [&](int row) { return colperm ? ((row & 63) << 2) + (row >> 6) : row; };
 
   // Byte offsets of this wave's TM rows: first row + i * row bytes, clamped to the last row of A
   // (rows past M recompute row M-1 and are not stored).  Three SGPRs; the eight offsets are
@@ -260,7 +339,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
     for (int t = 0; t < PPT; ++t) {
       const int idx = t * Cfg::THREADS + tid;
       const int row = idx / QPR;
-      const uint32_t n = (uint32_t)(n0 + row);
+      const uint32_t n = (uint32_t)(n0 + tile_col(row));
       // pooled ordering: a column is real iff its window exists (N = 4 * windows, but the
       // columns of the last tile's missing windows are interleaved with real ones)
       const uint32_t wdx = (n >> 8) * 64u + (n & 63u);
@@ -288,7 +367,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
     for (int t = 0; t < PPT; ++t) {
       const int idx = t * Cfg::THREADS + tid;
       const int row = idx / QPR;
-      const uint32_t n = (uint32_t)(n0 + row);
+      const uint32_t n = (uint32_t)(n0 + tile_col(row));
       const uint32_t wdx = (n >> 8) * 64u + (n & 63u);
       const bool ok = idx < Cfg::PIECES && (p.g.pool ? wdx < (uint32_t)(p.N >> 2) : n < (uint32_t)p.N);
       uint32_t img = 0;
@@ -374,7 +453,7 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
       const int w0 = wbase + 2 * q;
       u32x4 v = {0u, 0u, 0u, 0u};
       if constexpr (BMODE == 0) {
-        const int n = n0 + row;
+        const int n = n0 + tile_col(row);
         if (idx < Cfg::PIECES && n < p.N && w0 <= last_w) {
           const uint64_t *src = p.B + (int64_t)n * p.ldb + w0;
           if (p.b_vec16 && !(wbase & 1) && w0 + 1 <= last_w) {
@@ -617,7 +696,12 @@ __global__ __launch_bounds__(64 * WM * WN, MINW) void xnor_gemm_kernel(GemmParam
   // ---- store ------------------------------------------------------------------------
   __builtin_amdgcn_s_setprio(3);
   if constexpr (EMODE == 0) {
-    store_tile<TN>(acc, m0, n0 + wn * 64 * TN + lane);
+    if constexpr (TN == 4 && WN == 1) {
+      if (colperm) store_tile_x4(acc, m0, n0 + 4 * lane);
+      else store_tile<TN>(acc, m0, n0 + lane);
+    } else {
+      store_tile<TN>(acc, m0, n0 + wn * 64 * TN + lane);
+    }
   } else {
     // Binarizing epilogue.  Row m is output channel m; the workgroup's 8 * WM rows are one
     // 64-bit channel word (WM = 8), or one 32-bit half of it (WM = 4), of every pixel in its
@@ -1017,6 +1101,12 @@ static bnn_status launch_cfg(GemmParams &p, int bmode, int emode, hipStream_t s,
   // share a SIMD (4 per compute unit); with fewer they cost issue slots.
   const int64_t waves = blocks * (Cfg::THREADS / 64);
   const bool yield = waves >= 2 * 4 * (int64_t)p.n_cu;
+  // 256-column tiles writing int32 / fp32: four consecutive columns per lane and 16-byte stores where
+  // every group of four columns is whole, inside one image and 16-byte aligned
+  p.colperm = (emode == 0 && TN == 4 && WN == 1 && (p.N & 3) == 0 && (!p.C || (p.ldc & 3) == 0) &&
+               (!p.Y || (p.ldy & 3) == 0) && (p.img_stride == 0 || ((p.OHW & 3u) == 0 && (p.img_stride & 3) == 0)))
+                  ? 1
+                  : 0;
   if constexpr ((TN == 4 || TN == 2) && (WM == 8 || WM == 4) && WN == 1) {
     if (emode == 1) {
       if (bmode == 0 || (p.g.pool && TN != 4)) return BNN_ERR_UNSUPPORTED;

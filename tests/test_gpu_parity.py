@@ -119,6 +119,42 @@ def test_gemm_ragged_tiles(M, N, cfg):
     _gemm_case(M, N, 300, seed=M * 1000 + N + cfg, cfg=cfg)
 
 
+@pytest.mark.parametrize("cfg", [1, 3])
+@pytest.mark.parametrize("K", [1, 63, 64, 130, 192, 200, 256, 400, 512, 704, 1152, 2304 + 17])
+def test_gemm_four_columns_per_lane_tiles_k_sweep(K, cfg):
+    """N a multiple of 4: the 256-column tiles take four consecutive columns per lane and store 16 bytes
+    (N = 150 in the sweep above takes the one-column form); every kind of K tail, one and several tiles."""
+    print(f"gemm four-column tiles K={K} cfg={cfg}", flush=True)
+    _gemm_case(37, 152, K, seed=K * 11 + cfg, cfg=cfg)
+    _gemm_case(70, 516, K, seed=K * 13 + cfg, cfg=cfg)
+
+
+@pytest.mark.parametrize("lean", [1, 0])
+@pytest.mark.parametrize("cfg", [1, 3])
+@pytest.mark.parametrize("case", [(3, 128, 8, 8, 40, 3, 3, 1, 1, 1, 1), (3, 128, 10, 10, 70, 3, 3, 1, 1, 1, 1),
+                                  (2, 64, 7, 9, 33, 3, 3, 1, 1, 1, 1), (5, 192, 6, 6, 130, 3, 3, 2, 2, 1, 1),
+                                  (4, 128, 12, 12, 64, 1, 1, 2, 2, 0, 0), (7, 256, 6, 6, 65, 3, 3, 1, 1, 1, 1)])
+def test_conv2d_four_columns_per_lane_tiles(case, cfg, lean):
+    """int32 and fp32 NCHW outputs of the 256-column tiles with both gathers: maps whose pixel count is a
+    multiple of 4 (16-byte stores, four-pixel groups that must not straddle images: 64, 100 and 36 pixels
+    per image against 256 columns per tile) and maps where it is not (63 and 9: one column per lane)."""
+    print(f"conv2d four-column tiles case={case} cfg={cfg} lean={lean}", flush=True)
+    N, C, H, W, D, kH, kW, sH, sW, pH, pW = case
+    d = inputs.conv_inputs(inputs.ConvShape(*case), seed=sum(case) + 31)
+    x = inputs.inject_specials(d["x"], 8, frac=0.01)
+    xp = _u64dev(oracle.pack_nhwc(x))
+    wp = B.bnn_pack_conv_weight(dev(d["w"]))
+    sc, bi = dev(d["scale"]), dev(d["bias"])
+    st, pd = (sH, sW), (pH, pW)
+    ref = oracle.conv2d_pm1(x, d["w"], st, pd)
+    assert np.array_equal(host(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, out="i32", cfg=cfg, lean=lean)), ref)
+    yref = oracle.scale_bias(ref, d["scale"], d["bias"], "nchw")
+    got = host(B.bnn_conv2d_packed(xp, wp, C, D, kH, kW, st, pd, scale=sc, bias=bi, out="f32", cfg=cfg, lean=lean))
+    assert np.array_equal(got, yref)
+    oi, of = B.bnn_conv2d(dev(x), wp, D, kH, kW, st, pd, sc, bi, want_int=True, cfg=cfg, lean=lean)
+    assert np.array_equal(host(oi), ref) and np.array_equal(host(of), yref)
+
+
 @pytest.mark.parametrize("cfg", [-1, 10, 11, 12])
 @pytest.mark.parametrize("M,N,K", [(37, 152, 200), (8, 4, 65), (64, 256, 256), (130, 1028, 193), (257, 516, 128),
                                    (33, 260, 100), (70, 2052, 255), (5, 64, 129)])
